@@ -1,0 +1,94 @@
+/*
+ * tg_oracle.h -- CPU oracle for the TernGrad hot path (arXiv 1705.07878).
+ *
+ * TEST INFRASTRUCTURE, NOT THE PRODUCT.  This is a plain, slow, obviously
+ * correct host implementation of what the hot path computes, written from the
+ * paper's definitions (Section 3.1 Eq. 1-4, Section 3.3 Eq. 5, Algorithm 1).
+ * Only the test-suite, the smoke check and the benchmark's cpu_baseline leg
+ * may call it.  It shares no source, header, table or helper with the HIP
+ * library and neither side includes the other.
+ *
+ * All pointers are HOST pointers.  All reductions are fp64, two-pass.
+ *
+ * Notation (paper): g = gradient vector of one layer of one worker, s = scaler
+ * (Eq. 2 / Eq. 4), b = Bernoulli vector (Eq. 3), c*sigma = clip threshold
+ * (Eq. 5), N = W = number of workers.  "Layer" = one tensor: weights and
+ * biases are separate layers (Section 3.3, layer-wise ternarizing).
+ * Layers are given as a flat concatenation with an offset table
+ * off[0..L], off[0] = 0, off[L] = n, non-decreasing.
+ *
+ * Parity pins (see tests/test_oracle_*.py):
+ *   - Philox4x32-10 block function: pinned against an independent public
+ *     implementation compiled at test time.
+ *   - Bernoulli decision: exhaustive enumeration of the 65,536 random fields.
+ *   - population-vs-sample standard deviation: PARITY UNPINNED (the paper only
+ *     says "standard deviation"; population, mean-subtracted is the reading).
+ */
+#ifndef TG_ORACLE_H
+#define TG_ORACLE_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* Number of OpenMP threads the element-wise loops may use (default 1).
+ * Results do not depend on it: the generator is counter based. Returns the
+ * value now in force. */
+int tgo_set_threads(int n_threads);
+
+/* Philox4x32 with 10 rounds (Salmon et al., SC'11): one 128-bit counter block
+ * under a 64-bit key -> four 32-bit words. */
+void tgo_philox4x32_10(const uint32_t ctr[4], const uint32_t key[2], uint32_t out[4]);
+
+/* The 16-bit random field r in [0, 65535] assigned to flat element index e of
+ * `worker` at `step` under `seed`:
+ *   block q = e >> 3 ; counter = (lo32(q), hi32(q), worker, step) ;
+ *   key = (lo32(seed), hi32(seed)) ; h = e & 7 ;
+ *   r = (out[h >> 1] >> (16 * (h & 1))) & 0xFFFF.
+ * The uniform variate is u = (r + 1/2) / 2^16 = (2r + 1) / 2^17. */
+uint32_t tgo_random_field(uint64_t seed, uint32_t step, uint32_t worker, uint64_t e);
+
+/* Eq. 3: the Bernoulli draw b = [u * s < a], taken in fp32 as
+ *   s17 = fl32(s * 2^-17) ; thr = fl32((float)(2r + 1) * s17) ; b = (thr < a).
+ * a = |clipped gradient|.  No division: s = 0 gives b = (0 < a). */
+int tgo_bernoulli(uint32_t r, float s, float a);
+
+/* Eq. 5 + Eq. 2, one worker.  Per layer l (fp64, two passes):
+ *   mu = mean(g_l) ; sigma = sqrt(mean((g_l - mu)^2)) ; tau_l = (float)(c * sigma)
+ *   s_local_l = min(max|g_l|, tau_l)   (= max |clip(g_l)|)
+ * c <= 0 or c = +inf means "no clipping": tau_l = +inf, s_local_l = max|g_l|.
+ * An empty layer gets sigma = 0 and max = 0.
+ * g: [n] ; tau, s_local: [L]. */
+void tgo_clip_stats(const float* g, int64_t n_layers, const int64_t* off, float c,
+                    float* tau, float* s_local);
+
+/* Eq. 4: s_shared[l] = max_w s_local[w*L + l]. */
+void tgo_share_scalers(const float* s_local, int n_workers, int64_t n_layers, float* s_shared);
+
+/* Eq. 1 + Eq. 3 + Eq. 5 + 2-bit code, one worker.  For flat index e in layer l:
+ *   a = min(|g_e|, tau_l) ; r = tgo_random_field(seed, step, worker, e)
+ *   b = tgo_bernoulli(r, s_shared_l, a) ; t = b ? (signbit(g_e) ? -1 : +1) : 0
+ * code = t & 3 (00 = 0, 01 = +1, 11 = -1), stored LSB first, four per byte:
+ * byte e >> 2 holds code << 2*(e & 3).  Writes exactly ceil(n/4) bytes; pad
+ * codes in the last byte are 00.  tau: this worker's [L]; s_shared: [L]. */
+void tgo_ternarize_pack(const float* g, int64_t n_layers, const int64_t* off,
+                        const float* tau, const float* s_shared,
+                        uint64_t seed, uint32_t step, uint32_t worker, uint8_t* codes);
+
+/* The ternary value t in {-2,-1,0,+1} held by element e of a code buffer: the
+ * 2-bit field read as a two's-complement number (10 = -2 is never produced by
+ * tgo_ternarize_pack and is decoded literally). */
+int tgo_code_at(const uint8_t* codes, int64_t e);
+
+/* Algorithm 1, server line, with the shared scaler:
+ *   k_e = sum_w t_w(e) (exact integer) ; avg_e = (float)((double)k_e * s_shared_l / W).
+ * codes: W host pointers to ceil(n/4)-byte buffers; avg: [n]. */
+void tgo_unpack_average(const uint8_t* const* codes, int n_workers, int64_t n_layers,
+                        const int64_t* off, const float* s_shared, float* avg);
+
+#ifdef __cplusplus
+}
+#endif
+#endif

@@ -1,0 +1,374 @@
+"""Pins for the CPU oracle: what the paper and the mathematics fix.
+
+None of these tests touches the HIP library.  Each checks the oracle against
+something other than itself: an independent public Philox implementation,
+closed forms for the Gaussian, numpy's library routines on special cases,
+exhaustive enumeration of the random field, Monte-Carlo expectations, and the
+numbers the paper prints (tests/golden/paper_values.json).
+"""
+import ctypes
+import json
+import math
+import os
+import shutil
+import subprocess
+
+import numpy as np
+import pytest
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+PAPER = json.load(open(os.path.join(HERE, "golden", "paper_values.json")))
+
+
+def decode(o, codes, n):
+    return np.array([o.code_at(codes, e) for e in range(n)], dtype=np.int64)
+
+
+# --------------------------------------------------------------------------
+# Philox4x32-10: canonical-ness, pinned to ATen's header-only engine
+# --------------------------------------------------------------------------
+ATEN_SHIM = r"""
+#include <ATen/core/PhiloxRNGEngine.h>
+#include <cstdint>
+extern "C" void aten_philox(uint64_t seed, uint64_t subsequence, uint64_t offset, uint32_t* out) {
+    at::Philox4_32 eng(seed, subsequence, offset);
+    for (int i = 0; i < 4; ++i) out[i] = eng();
+}
+"""
+
+
+@pytest.fixture(scope="module")
+def aten_philox(tmp_path_factory):
+    import torch
+    inc = os.path.join(os.path.dirname(torch.__file__), "include")
+    if shutil.which("g++") is None or not os.path.exists(os.path.join(inc, "ATen/core/PhiloxRNGEngine.h")):
+        pytest.skip("no independent Philox implementation available")
+    d = tmp_path_factory.mktemp("aten")
+    src = d / "shim.cpp"
+    src.write_text(ATEN_SHIM)
+    so = d / "libshim.so"
+    subprocess.run(["g++", "-std=c++17", "-O1", "-shared", "-fPIC", "-I", inc, str(src), "-o", str(so)], check=True)
+    lib = ctypes.CDLL(str(so))
+    lib.aten_philox.argtypes = [ctypes.c_uint64, ctypes.c_uint64, ctypes.c_uint64, ctypes.POINTER(ctypes.c_uint32)]
+
+    def f(seed, subseq, offset):
+        out = (ctypes.c_uint32 * 4)()
+        lib.aten_philox(seed, subseq, offset, out)
+        return [int(x) for x in out]
+    return f
+
+
+def test_philox_block_matches_independent_implementation(oracle, aten_philox):
+    # ATen: key = (lo, hi) of seed; counter = (lo, hi of offset, lo, hi of subsequence)
+    rng = np.random.default_rng(1)
+    cases = [(0, 0, 0), (1, 0, 0), (0, 1, 0), (0, 0, 1), (2**64 - 1, 2**64 - 1, 2**64 - 1)]
+    cases += [tuple(int(x) for x in rng.integers(0, 2**63, size=3, dtype=np.uint64)) for _ in range(200)]
+    for seed, sub, offs in cases:
+        ctr = [offs & 0xFFFFFFFF, offs >> 32, sub & 0xFFFFFFFF, sub >> 32]
+        key = [seed & 0xFFFFFFFF, seed >> 32]
+        assert oracle.philox4x32_10(ctr, key) == aten_philox(seed, sub, offs), (seed, sub, offs)
+
+
+def test_random_field_layout_against_independent_blocks(oracle, aten_philox):
+    """element e -> block e>>3, counter (q, worker, step), 16-bit field e&7 (low half first)."""
+    seed, step, worker = 0x0123456789ABCDEF, 7, 3
+    for e in list(range(40)) + [2**35 + 5, 2**40 + 13]:
+        q = e >> 3
+        words = aten_philox(seed, worker | (step << 32), q)
+        h = e & 7
+        want = (words[h >> 1] >> (16 * (h & 1))) & 0xFFFF
+        assert oracle.random_field(seed, step, worker, e) == want
+
+
+def test_random_field_statistics(oracle):
+    m = 1 << 16
+    r = np.array([oracle.random_field(11, 0, 0, e) for e in range(m)], dtype=np.uint32)
+    assert r.max() < 65536
+    # every bit balanced within 5 sigma
+    for bit in range(16):
+        ones = int(((r >> bit) & 1).sum())
+        assert abs(ones - m / 2) < 5 * math.sqrt(m / 4), bit
+    # chi-square on the top byte (256 cells)
+    cnt = np.bincount(r >> 8, minlength=256)
+    chi2 = float(((cnt - m / 256) ** 2 / (m / 256)).sum())
+    assert chi2 < 255 + 6 * math.sqrt(2 * 255)
+    # different worker / step / seed give different streams
+    a = [oracle.random_field(11, 0, 0, e) for e in range(64)]
+    assert a != [oracle.random_field(11, 0, 1, e) for e in range(64)]
+    assert a != [oracle.random_field(11, 1, 0, e) for e in range(64)]
+    assert a != [oracle.random_field(12, 0, 0, e) for e in range(64)]
+    assert a != [oracle.random_field(11 + 2**32, 0, 0, e) for e in range(64)]
+
+
+# --------------------------------------------------------------------------
+# Eq. 3: Bernoulli(|g|/s), exhaustive over the 65,536 random fields
+# --------------------------------------------------------------------------
+@pytest.mark.parametrize("s,a", [(1.0, 0.5), (1.0, 0.3), (0.0123, 0.0001), (3.7e-4, 3.6e-4),
+                                 (1.0, 1e-5), (7.0, 7.0), (1.0, 0.0), (2.5e-3, 1e-9)])
+def test_bernoulli_probability_exact(oracle, s, a):
+    s32, a32 = np.float32(s), np.float32(a)
+    fires = sum(oracle.bernoulli(r, s32, a32) for r in range(65536))
+    p = fires / 65536.0
+    want = float(a32) / float(s32)
+    # u = (r + 1/2) / 2^16 is a midpoint grid: P is a/s rounded to the grid
+    assert abs(p - want) <= 2.0 ** -17 + 2.0 ** -22, (p, want)
+    if a32 == s32:
+        assert fires == 65536           # |g| = s keeps its sign with probability 1
+    if a32 == 0:
+        assert fires == 0               # zero gradient encodes to 0
+
+
+def test_bernoulli_is_monotone_in_r_and_has_no_division(oracle):
+    s, a = np.float32(0.37), np.float32(0.11)
+    b = [oracle.bernoulli(r, s, a) for r in range(65536)]
+    assert b == sorted(b, reverse=True)          # fires exactly for small u
+    # s = 0 cannot divide: decision is (0 < a)
+    assert oracle.bernoulli(123, 0.0, 0.0) == 0
+    assert oracle.bernoulli(123, 0.0, 1.0) == 1
+
+
+# --------------------------------------------------------------------------
+# Eq. 1: alphabet, certainty at |g| = s, zeros, sign
+# --------------------------------------------------------------------------
+def test_alphabet_argmax_zero_and_sign(oracle):
+    rng = np.random.default_rng(5)
+    n = 13
+    off = np.array([0, n])
+    for seed in range(300):
+        g = rng.normal(size=n).astype(np.float32)
+        g[3] = 0.0
+        g[4] = -0.0
+        tau, s = oracle.clip_stats(g, off, 0.0)          # no clip: s = max|g|
+        assert np.isinf(tau[0]) and s[0] == np.abs(g).max()
+        codes = oracle.ternarize_pack(g, off, tau, s, seed, 0, 0)
+        t = decode(oracle, codes, n)
+        assert set(t.tolist()) <= {-1, 0, 1}
+        k = int(np.abs(g).argmax())
+        assert t[k] == (1 if g[k] > 0 else -1)           # P = 1 at |g| = s
+        assert t[3] == 0 and t[4] == 0
+        nz = t != 0
+        assert np.all(np.sign(g[nz]) == t[nz])           # sign(g) where b = 1
+        avg = oracle.unpack_average([codes], off, s)     # W = 1: decode
+        assert set(np.unique(avg).tolist()) <= {-float(s[0]), 0.0, float(s[0])}
+
+
+def test_ternarize_agrees_with_its_parts(oracle):
+    rng = np.random.default_rng(6)
+    sizes = [5, 1, 0, 9, 16, 3]
+    off = np.concatenate([[0], np.cumsum(sizes)])
+    n = int(off[-1])
+    g = (rng.normal(size=n) * 1e-2).astype(np.float32)
+    tau = np.abs(rng.normal(size=len(sizes))).astype(np.float32) * 2e-2
+    s = np.abs(rng.normal(size=len(sizes))).astype(np.float32) * 3e-2
+    codes = oracle.ternarize_pack(g, off, tau, s, 99, 4, 2)
+    assert codes.size == (n + 3) // 4
+    lay = np.repeat(np.arange(len(sizes)), sizes)
+    for e in range(n):
+        a = min(abs(np.float32(g[e])), tau[lay[e]])
+        b = oracle.bernoulli(oracle.random_field(99, 4, 2, e), s[lay[e]], a)
+        want = 0 if not b else (-1 if g[e] < 0 else 1)
+        assert oracle.code_at(codes, e) == want
+    for e in range(n, 4 * codes.size):                  # pad codes are 00
+        assert oracle.code_at(codes, e) == 0
+
+
+# --------------------------------------------------------------------------
+# unbiasedness (Section 3.2, expectation of the ternary gradient) and the
+# second moment used in the proof of Theorem 1: E||g~||^2 = s * ||g||_1
+# --------------------------------------------------------------------------
+def test_monte_carlo_unbiased_and_second_moment(oracle):
+    rng = np.random.default_rng(7)
+    n, M = 32, 20000
+    off = np.array([0, 20, n])
+    g = rng.normal(size=n).astype(np.float32)
+    g[:20] *= 1e-3
+    g[5] = 8e-3                                          # will be clipped
+    tau, s_loc = oracle.clip_stats(g, off, 2.5)
+    s = s_loc.copy()
+    lay = np.repeat([0, 1], [20, n - 20])
+    a = np.minimum(np.abs(g), tau[lay]).astype(np.float64)
+    gc = np.sign(g) * a                                  # the clipped gradient
+    acc = np.zeros(n)
+    nnz = 0
+    for m in range(M):
+        codes = oracle.ternarize_pack(g, off, tau, s, seed=m, step=m % 3, worker=m % 5)
+        t = decode(oracle, codes, n)
+        acc += t * s[lay]
+        nnz += int((t != 0).sum())
+    mean = acc / M
+    sd = np.sqrt(np.maximum(s[lay] * a - a * a, 1e-30) / M)
+    z = np.abs(mean - gc) / sd
+    assert z.max() < 5.0, z
+    p = a / s[lay]
+    assert abs(nnz / M - p.sum()) < 5 * math.sqrt((p * (1 - p)).sum() / M)
+
+
+# --------------------------------------------------------------------------
+# Eq. 5 + Eq. 2: clip threshold and scaler
+# --------------------------------------------------------------------------
+def _Q(c):
+    return 0.5 * math.erfc(c / math.sqrt(2))
+
+
+def test_clip_stats_against_numpy_and_gaussian_closed_forms(oracle):
+    rng = np.random.default_rng(8)
+    n, c = 1_000_000, PAPER["clip_constant"]["value"]
+    x = (rng.normal(size=n) * 3e-3 + 1e-4).astype(np.float32)
+    off = np.array([0, n])
+    tau, s = oracle.clip_stats(x, off, c)
+    # library special case: population std, mean subtracted
+    assert tau[0] == np.float32(c * np.std(x.astype(np.float64)))
+    assert s[0] == min(np.abs(x).max(), tau[0])
+    # the clipped vector, by its definition
+    z = x.astype(np.float64) - x.astype(np.float64).mean()
+    t = float(c * z.std())
+    f = np.clip(z, -t, t)
+    ratio = np.linalg.norm(f) / np.linalg.norm(z)
+    cosang = float(f @ z) / (np.linalg.norm(f) * np.linalg.norm(z))
+    angle = math.degrees(math.acos(cosang))
+    phi = math.exp(-0.5 * c * c) / math.sqrt(2 * math.pi)
+    ratio_cf = math.sqrt(1 - 2 * (_Q(c) + c * phi - c * c * _Q(c)))
+    angle_cf = math.degrees(math.acos((1 - 2 * _Q(c)) / ratio_cf))
+    assert abs(ratio - ratio_cf) < 2e-3 and abs(angle - angle_cf) < 0.1
+    assert abs((np.abs(z) > t).mean() - 2 * _Q(c)) < 1e-3
+    # the paper's own numerical analysis: length 1.0-1.5 % shorter, direction 2-3 degrees
+    lo, hi = PAPER["clip_length_change_percent"]["low"], PAPER["clip_length_change_percent"]["high"]
+    assert lo <= 100 * (1 - ratio) <= hi
+    lo, hi = PAPER["clip_direction_change_degrees"]["low"], PAPER["clip_direction_change_degrees"]["high"]
+    assert lo <= angle <= hi
+
+
+def test_clip_stats_layerwise_and_edge_cases(oracle):
+    rng = np.random.default_rng(9)
+    sizes = [1, 2, 3, 0, 4, 5, 15, 16, 17, 1000]
+    off = np.concatenate([[0], np.cumsum(sizes)])
+    g = (rng.normal(size=int(off[-1])) * 1e-2 + 5e-3).astype(np.float32)
+    tau, s = oracle.clip_stats(g, off, 2.5)
+    for l, sz in enumerate(sizes):
+        seg = g[off[l]:off[l + 1]].astype(np.float64)
+        if sz == 0:
+            assert tau[l] == 0 and s[l] == 0
+            continue
+        assert tau[l] == np.float32(2.5 * seg.std()), l          # population (ddof = 0)
+        assert s[l] == min(np.float32(np.abs(seg).max()), tau[l])
+    assert tau[0] == 0 and s[0] == 0                              # one element: sigma = 0
+    # constant layer: sigma exactly 0; large mean does not leak into sigma
+    const = np.full(77, 0.3, np.float32)
+    tau, s = oracle.clip_stats(const, np.array([0, 77]), 2.5)
+    assert tau[0] == 0 and s[0] == 0
+    # no-clip variants (TernGrad-noclip row of Table 2): c <= 0 or +inf
+    for c in (0.0, -1.0, float("inf")):
+        tau, s = oracle.clip_stats(g, off, c)
+        assert np.all(np.isinf(tau))
+        assert s[9] == np.abs(g[off[9]:]).max()
+
+
+def test_share_scalers_is_max_over_workers(oracle):
+    rng = np.random.default_rng(10)
+    for W, L in [(1, 1), (2, 8), (8, 116), (64, 3)]:
+        s_local = np.abs(rng.normal(size=(W, L))).astype(np.float32)
+        assert np.array_equal(oracle.share_scalers(s_local), s_local.max(axis=0))     # Eq. 4
+
+
+# --------------------------------------------------------------------------
+# 2-bit code: exact round trip, size, average
+# --------------------------------------------------------------------------
+def _forced(oracle, t, s=0.5):
+    """codes for a prescribed ternary vector t: g = t * s, no clip, P = 1 or 0"""
+    t = np.asarray(t)
+    g = (t * s).astype(np.float32)
+    off = np.array([0, t.size])
+    tau = np.array([np.inf], np.float32)
+    return oracle.ternarize_pack(g, off, tau, np.array([s], np.float32), 3, 1, 0)
+
+
+def test_pack_roundtrip_all_81_bytes_and_ragged_lengths(oracle):
+    vals = [0, 1, -1]
+    for i in range(81):
+        t = [vals[(i // 3 ** j) % 3] for j in range(4)]
+        codes = _forced(oracle, t)
+        assert codes.size == 1
+        want = sum(((v & 3) << (2 * j)) for j, v in enumerate(t))     # 00 / 01 / 11, LSB first
+        assert int(codes[0]) == want
+        assert decode(oracle, codes, 4).tolist() == t
+    rng = np.random.default_rng(11)
+    for n in list(range(1, 34)) + [1000, 1023, 1025]:
+        t = rng.integers(-1, 2, size=n)
+        codes = _forced(oracle, t)
+        assert codes.size == (n + 3) // 4
+        assert decode(oracle, codes, n).tolist() == t.tolist()
+        # the paper's 16x: fp32 bytes over code bytes (Section 3.1), exact when 4 | n
+        if n % 4 == 0:
+            assert 4 * n / codes.size == PAPER["worker_to_server_reduction_2bit"]["value"]
+    # printed truncated to two decimals
+    assert 0 <= 32 / math.log2(3) - PAPER["worker_to_server_reduction_ideal"]["value"] < 1e-2
+
+
+def test_unpack_average_levels_mean_and_w1(oracle):
+    rng = np.random.default_rng(12)
+    sizes = [7, 64, 1, 130]
+    off = np.concatenate([[0], np.cumsum(sizes)])
+    n = int(off[-1])
+    lay = np.repeat(np.arange(len(sizes)), sizes)
+    for W in (1, 2, 3, 4, 8, 64):
+        s = (np.abs(rng.normal(size=len(sizes))) + 0.1).astype(np.float32)
+        ts = [rng.integers(-1, 2, size=n) for _ in range(W)]
+        codes = [_forced(oracle, t) for t in ts]
+        avg = oracle.unpack_average(codes, off, s)
+        k = np.sum(ts, axis=0)
+        # textbook: the mean of the decoded ternary gradients (Algorithm 1, server line)
+        want = np.mean([t * s[lay].astype(np.float64) for t in ts], axis=0)
+        assert np.allclose(avg, want, rtol=2e-7, atol=0)
+        assert np.all(avg[k == 0] == 0)
+        for l in range(len(sizes)):
+            lv = np.unique(avg[off[l]:off[l + 1]])
+            assert lv.size <= 2 * W + 1                                   # at most 2N+1 levels
+            ratio = lv.astype(np.float64) * W / float(s[l])
+            assert np.allclose(ratio, np.round(ratio), atol=1e-5)         # all of the form k*s/N
+        if W == 1:
+            assert np.array_equal(avg, (ts[0] * s[lay]).astype(np.float32))
+
+
+def test_code_10_decodes_as_twos_complement(oracle):
+    codes = np.array([0b10_11_01_00], np.uint8)
+    assert [oracle.code_at(codes, e) for e in range(4)] == [0, 1, -1, -2]
+
+
+def test_threads_do_not_change_results(oracle):
+    rng = np.random.default_rng(13)
+    sizes = [1000, 37, 5000]
+    off = np.concatenate([[0], np.cumsum(sizes)])
+    g = (rng.normal(size=int(off[-1])) * 1e-2).astype(np.float32)
+    oracle.set_threads(1)
+    tau1, s1 = oracle.clip_stats(g, off, 2.5)
+    c1 = oracle.ternarize_pack(g, off, tau1, s1, 5, 6, 7)
+    a1 = oracle.unpack_average([c1, c1], off, s1)
+    try:
+        oracle.set_threads(4)
+        tau4, s4 = oracle.clip_stats(g, off, 2.5)
+        c4 = oracle.ternarize_pack(g, off, tau1, s1, 5, 6, 7)
+        a4 = oracle.unpack_average([c4, c4], off, s1)
+    finally:
+        oracle.set_threads(1)
+    assert np.allclose(tau1, tau4, rtol=1e-7) and np.array_equal(s1 >= 0, s4 >= 0)
+    assert np.array_equal(c1, c4) and np.array_equal(a1, a4)
+
+
+def test_zero_fraction_on_gaussian_matches_expectation(oracle):
+    """E[#nonzero] = sum a/s: for N(0,1) clipped at c sigma the zero share is
+    1 - E[min(|Z|,c)]/c = 68.2 % at c = 2.5 (the paper reports 71.32 % for real
+    AlexNet fc6 gradients: same order)."""
+    rng = np.random.default_rng(14)
+    n = 400_000
+    g = (rng.normal(size=n) * 2e-3).astype(np.float32)
+    off = np.array([0, n])
+    tau, s = oracle.clip_stats(g, off, 2.5)
+    codes = oracle.ternarize_pack(g, off, tau, s, 0, 0, 0)
+    lut = np.array([bin(b & 0x55).count("1") for b in range(256)])
+    nz = int(lut[codes].sum())
+    c = 2.5
+    phi = math.exp(-0.5 * c * c) / math.sqrt(2 * math.pi)
+    e_min = 2 * (1 / math.sqrt(2 * math.pi) - phi) + 2 * c * _Q(c)
+    want_zero = 1 - e_min / c
+    assert abs((1 - nz / n) - want_zero) < 5e-3
+    assert abs(100 * want_zero - PAPER["alexnet_fc6_zero_fraction_percent"]["value"]) < 5

@@ -1,0 +1,149 @@
+/*
+ * terngrad.h -- C ABI of libterngrad.so: the data-parallel hot path of TernGrad
+ * (layer-wise stochastic gradient ternarization, arXiv 1705.07878) on MI355X.
+ *
+ * One training step, worker i of N (Algorithm 1), maps onto four calls:
+ *
+ *   tg_clip_stats      Eq. 5 + Eq. 2   clip threshold c*sigma and local scaler, per layer
+ *   tg_share_scalers   Eq. 4           shared scaler = max over workers, per layer
+ *   tg_ternarize_pack  Eq. 1, 3, 5     clip -> Bernoulli(|g|/s) -> sign -> 2-bit code
+ *   tg_unpack_average  Alg. 1, server  decode N code buffers, sum, rescale by s/N
+ *
+ * "Layer" means one tensor: the gradients of weights and of biases are
+ * ternarized separately (Section 3.3, layer-wise ternarizing).  A worker's
+ * gradient is the flat fp32 concatenation of its L layers; off[0..L] holds the
+ * element offsets (off[0] = 0, off[L] = n, non-decreasing; empty layers allowed).
+ * Finer buckets than a layer (Section 3.3) are expressed by a finer table.
+ *
+ * Conventions
+ *   - Every function returns a tg_status; nothing throws, prints or sets errno.
+ *   - "dev" pointers are device (HBM) pointers, "host" pointers are host memory.
+ *     The caller owns every gradient, scaler, code and output buffer.  A plan
+ *     owns only its own tables and reduction workspace.
+ *   - Gradient and average pointers must be 16-byte aligned, code pointers
+ *     4-byte aligned.
+ *   - Compute calls are asynchronous on `stream` (a hipStream_t passed as
+ *     void*; NULL = the default stream), never synchronise and never allocate.
+ *   - The N workers of one machine are batched: arrays of N device pointers are
+ *     passed from the host and one launch covers all of them.  A real
+ *     one-worker-per-GPU deployment calls with n_workers = 1 and
+ *     worker_base = its rank.
+ *   - Inputs must be finite; the result for NaN/Inf gradients is unspecified
+ *     (never a fault).
+ *
+ * Definitions the paper leaves open (and this library fixes)
+ *   - sigma is the population standard deviation of the layer, mean subtracted.
+ *   - Clipping precedes ternarizing on every worker (Section 3.3), so the
+ *     scaler is the max-abs of the CLIPPED layer: s_local = min(max|g|, c*sigma).
+ *   - Random numbers: Philox4x32-10, key = (lo32, hi32) of seed, counter =
+ *     (lo32(q), hi32(q), worker, step) with q = e >> 3 for flat element index e;
+ *     element e uses the 16-bit field (e & 7) of the 128-bit output, low half
+ *     of word 0 first:  r = (out[(e&7)>>1] >> 16*(e&1)) & 0xFFFF,
+ *     u = (2r + 1) / 2^17.
+ *   - Eq. 3 is taken without division, in fp32:
+ *       s17 = fl(s * 2^-17) ; b = [ fl((float)(2r+1) * s17) < min(|g|, c*sigma) ].
+ *   - 2-bit codes: 00 = 0, 01 = +1, 11 = -1 (two's complement), four per byte,
+ *     least significant pair first, flat over the layers; pad codes are 00.
+ *     10 is never produced and decodes as -2.
+ */
+#ifndef TERNGRAD_H
+#define TERNGRAD_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct tg_plan tg_plan;
+
+typedef enum {
+    TG_OK = 0,
+    TG_ERR_INVALID_ARG = -1,      /* null pointer, bad size, offsets not monotone, ... */
+    TG_ERR_ALIGNMENT = -2,        /* a device pointer is not aligned as required      */
+    TG_ERR_TOO_MANY_WORKERS = -3, /* n_workers > plan's max_workers or TG_MAX_WORKERS  */
+    TG_ERR_HIP = -4,              /* a HIP call failed: see tg_last_hip_error()        */
+    TG_ERR_ALLOC = -5             /* host or device allocation failed                  */
+} tg_status;
+
+/* The paper trains with up to N = 64 workers (Section 4.1, LeNet). */
+#define TG_MAX_WORKERS 64
+
+/* ---- plan: the offset table of one model, uploaded once ------------------- */
+
+/* Builds the tables for a model with `n_layers` tensors whose element offsets
+ * are offsets[0..n_layers] (host), uploads them to the current device and
+ * reserves the reduction workspace of tg_clip_stats for up to `max_workers`
+ * workers per call.  Requires n_layers >= 1, offsets[0] = 0, offsets
+ * non-decreasing, offsets[n_layers] >= 1, 1 <= max_workers <= TG_MAX_WORKERS.
+ * Errors: TG_ERR_INVALID_ARG, TG_ERR_TOO_MANY_WORKERS, TG_ERR_ALLOC, TG_ERR_HIP. */
+tg_status tg_plan_create(int64_t n_layers, const int64_t* offsets, int max_workers, tg_plan** out);
+
+/* Frees the plan's device and host memory.  NULL is accepted. */
+tg_status tg_plan_destroy(tg_plan* plan);
+
+int64_t tg_num_elements(const tg_plan* plan); /* n, or -1 for NULL */
+int64_t tg_num_layers(const tg_plan* plan);   /* L, or -1 for NULL */
+/* Size in bytes a code buffer must have: ceil(n/4) rounded up to a multiple of
+ * 16.  The first ceil(n/4) bytes carry codes; the rest is written as 0. */
+int64_t tg_packed_bytes(const tg_plan* plan);
+
+const char* tg_strerror(int status);
+/* The hipError_t of the most recent failing HIP call on this thread (0 = none). */
+int tg_last_hip_error(void);
+
+/* Host-only: the tables tg_plan_create derives from an offset table, exported
+ * so that they can be checked without a GPU.
+ *   tile_layer[t]  = layer holding element t * tile (tile = *tile_elems)
+ *   seg[3*i..]     = (layer, begin, end) of the i-th reduction segment: a maximal
+ *                    run of elements inside one layer and one statistics chunk
+ *                    of *chunk_elems elements
+ * Pass NULL arrays (or too small capacities) to query the sizes only. */
+tg_status tg_describe_tables(int64_t n_layers, const int64_t* offsets,
+                             int64_t* tile_elems, int64_t* n_tiles, int32_t* tile_layer, int64_t tile_cap,
+                             int64_t* chunk_elems, int64_t* n_segments, int64_t* seg, int64_t seg_cap);
+
+/* ---- the four calls of the hot path --------------------------------------- */
+
+/* Eq. 5 and Eq. 2, for n_workers gradients in one launch.
+ *   grads    host array of n_workers dev pointers, each to n fp32
+ *   c        clip constant (the paper uses 2.5); c <= 0 or +inf = no clipping
+ *            (the "TernGrad-noclip" row of Table 2): tau = +inf, s_local = max|g|
+ *   tau      dev [n_workers][L] out: c * sigma of each layer of each worker
+ *   s_local  dev [n_workers][L] out: min(max|g|, tau)
+ * Sums are accumulated in fp64 about a per-layer pivot, in a fixed order:
+ * results are identical from run to run.  An empty layer gets tau = 0 (or
+ * +inf without clipping) and s_local = 0. */
+tg_status tg_clip_stats(tg_plan* plan, int n_workers, const float* const* grads, float c,
+                        float* tau, float* s_local, void* stream);
+
+/* Eq. 4: s_shared[l] = max_w s_local[w][l].
+ *   s_local  dev [n_workers][L] in ; s_shared dev [L] out.
+ * Across GPUs this is the max-all-reduce of L floats per worker (the "2N
+ * floating scalars" of Section 3.1); here the N rows sit in one buffer. */
+tg_status tg_share_scalers(tg_plan* plan, int n_workers, const float* s_local,
+                           float* s_shared, void* stream);
+
+/* Eq. 1 + 3 + 5 and the 2-bit encoding, for n_workers gradients in one launch.
+ *   grads        host array of n_workers dev pointers (n fp32 each)
+ *   tau          dev [n_workers][L] in (each worker clips with its own sigma)
+ *   s_shared     dev [L] in
+ *   seed, step   RNG key and iteration counter t; worker w of this call draws
+ *                with worker id worker_base + w
+ *   codes        host array of n_workers dev pointers, each to tg_packed_bytes() bytes, out */
+tg_status tg_ternarize_pack(tg_plan* plan, int n_workers, uint32_t worker_base,
+                            const float* const* grads, const float* tau, const float* s_shared,
+                            uint64_t seed, uint32_t step, uint8_t* const* codes, void* stream);
+
+/* Algorithm 1, server line: avg[e] = (sum_w t_w[e]) * (s_shared[layer(e)] / n_workers),
+ * the integer sum exact, one fp32 division per layer and one fp32 product per element.
+ *   codes     host array of n_workers dev pointers to code buffers, in
+ *   s_shared  dev [L] in
+ *   avg       dev [n] fp32 out (at most 2N+1 distinct values per layer) */
+tg_status tg_unpack_average(tg_plan* plan, int n_workers, const uint8_t* const* codes,
+                            const float* s_shared, float* avg, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif

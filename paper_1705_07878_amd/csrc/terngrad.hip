@@ -1,0 +1,338 @@
+// libterngrad.so: C ABI of the TernGrad hot path (see include/terngrad.h).
+// Host side: argument checks, the plan (offset tables + reduction workspace),
+// launch geometry.  Every step of the path runs in the HIP kernels included below.
+#include "../../include/terngrad.h"
+
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstdlib>
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include "tg_stats.hpp"
+#include "tg_ternarize.hpp"
+#include "tg_unpack.hpp"
+
+static_assert(TG_MAX_WORKERS == tg::kMaxWorkers, "header and kernels disagree on the worker limit");
+
+namespace {
+
+thread_local int g_last_hip_error = 0;
+
+bool hip_ok(hipError_t e) {
+    if (e == hipSuccess) return true;
+    g_last_hip_error = (int)e;
+    (void)hipGetLastError();
+    return false;
+}
+
+struct Tables {
+    int64_t n = 0, n_tiles = 0, n_chunks = 0;
+    std::vector<int32_t> tile_layer;
+    std::vector<int64_t> chunk_seg;   // [n_chunks+1]
+    std::vector<int32_t> seg_layer;
+    std::vector<int64_t> seg_begin, seg_end;
+    std::vector<int64_t> layer_seg;   // [L+1]
+};
+
+tg_status check_offsets(int64_t n_layers, const int64_t* off) {
+    if (n_layers < 1 || n_layers > (int64_t)1 << 24 || off == nullptr) return TG_ERR_INVALID_ARG;
+    if (off[0] != 0) return TG_ERR_INVALID_ARG;
+    for (int64_t l = 0; l < n_layers; ++l)
+        if (off[l + 1] < off[l]) return TG_ERR_INVALID_ARG;
+    if (off[n_layers] < 1 || off[n_layers] > ((int64_t)1 << 40)) return TG_ERR_INVALID_ARG;
+    return TG_OK;
+}
+
+void build_tables(int64_t L, const int64_t* off, Tables& T) {
+    const int64_t n = off[L];
+    const int64_t tile = (int64_t)1 << tg::kTileShift;
+    T.n = n;
+    T.n_tiles = (n + tile - 1) / tile;
+    T.n_chunks = (n + tg::kStatChunk - 1) / tg::kStatChunk;
+    T.tile_layer.resize((size_t)T.n_tiles);
+    int64_t l = 0;
+    for (int64_t t = 0; t < T.n_tiles; ++t) {
+        const int64_t e = t * tile;
+        while (e >= off[l + 1]) ++l;          // e < n = off[L]: stops at the layer that holds e
+        T.tile_layer[(size_t)t] = (int32_t)l;
+    }
+    T.chunk_seg.assign((size_t)T.n_chunks + 1, 0);
+    T.layer_seg.assign((size_t)L + 1, 0);
+    l = 0;
+    int64_t next_layer_mark = 0;              // layers < this already have layer_seg set
+    for (int64_t c = 0; c < T.n_chunks; ++c) {
+        T.chunk_seg[(size_t)c] = (int64_t)T.seg_layer.size();
+        const int64_t cb = c * tg::kStatChunk;
+        const int64_t ce = (cb + tg::kStatChunk < n) ? cb + tg::kStatChunk : n;
+        int64_t pos = cb;
+        while (pos < ce) {
+            while (pos >= off[l + 1]) ++l;
+            const int64_t end = off[l + 1] < ce ? off[l + 1] : ce;
+            while (next_layer_mark <= l) T.layer_seg[(size_t)next_layer_mark++] = (int64_t)T.seg_layer.size();
+            T.seg_layer.push_back((int32_t)l);
+            T.seg_begin.push_back(pos);
+            T.seg_end.push_back(end);
+            pos = end;
+        }
+    }
+    T.chunk_seg[(size_t)T.n_chunks] = (int64_t)T.seg_layer.size();
+    while (next_layer_mark <= L) T.layer_seg[(size_t)next_layer_mark++] = (int64_t)T.seg_layer.size();
+}
+
+template <class T>
+bool upload(T** dst, const std::vector<T>& src) {
+    const size_t bytes = (src.empty() ? 1 : src.size()) * sizeof(T);
+    if (!hip_ok(hipMalloc((void**)dst, bytes))) return false;
+    if (!src.empty() && !hip_ok(hipMemcpy(*dst, src.data(), src.size() * sizeof(T), hipMemcpyHostToDevice))) return false;
+    return true;
+}
+
+bool aligned(const void* p, uintptr_t a) { return ((uintptr_t)p & (a - 1)) == 0; }
+
+}  // namespace
+
+struct tg_plan {
+    int64_t n_layers = 0, n = 0, packed_bytes = 0, n_tiles = 0, n_chunks = 0, n_segs = 0;
+    int max_workers = 0;
+    int64_t* d_off = nullptr;
+    int32_t* d_tile_layer = nullptr;
+    int64_t* d_chunk_seg = nullptr;
+    int32_t* d_seg_layer = nullptr;
+    int64_t* d_seg_begin = nullptr;
+    int64_t* d_seg_end = nullptr;
+    int64_t* d_layer_seg = nullptr;
+    double* d_psum = nullptr;
+    double* d_psq = nullptr;
+    float* d_pmax = nullptr;
+};
+
+extern "C" {
+
+const char* tg_strerror(int status) {
+    switch (status) {
+        case TG_OK: return "ok";
+        case TG_ERR_INVALID_ARG: return "invalid argument";
+        case TG_ERR_ALIGNMENT: return "device pointer not aligned as required";
+        case TG_ERR_TOO_MANY_WORKERS: return "too many workers for this plan";
+        case TG_ERR_HIP: return "a HIP call failed (see tg_last_hip_error)";
+        case TG_ERR_ALLOC: return "allocation failed";
+        default: return "unknown status";
+    }
+}
+
+int tg_last_hip_error(void) { return g_last_hip_error; }
+
+tg_status tg_describe_tables(int64_t n_layers, const int64_t* offsets,
+                             int64_t* tile_elems, int64_t* n_tiles, int32_t* tile_layer, int64_t tile_cap,
+                             int64_t* chunk_elems, int64_t* n_segments, int64_t* seg, int64_t seg_cap) {
+    const tg_status st = check_offsets(n_layers, offsets);
+    if (st != TG_OK) return st;
+    Tables T;
+    try {
+        build_tables(n_layers, offsets, T);
+    } catch (const std::bad_alloc&) {
+        return TG_ERR_ALLOC;
+    }
+    if (tile_elems) *tile_elems = (int64_t)1 << tg::kTileShift;
+    if (chunk_elems) *chunk_elems = tg::kStatChunk;
+    if (n_tiles) *n_tiles = T.n_tiles;
+    if (n_segments) *n_segments = (int64_t)T.seg_layer.size();
+    if (tile_layer && tile_cap >= T.n_tiles)
+        std::memcpy(tile_layer, T.tile_layer.data(), (size_t)T.n_tiles * sizeof(int32_t));
+    if (seg && seg_cap >= (int64_t)T.seg_layer.size())
+        for (size_t i = 0; i < T.seg_layer.size(); ++i) {
+            seg[3 * i] = T.seg_layer[i];
+            seg[3 * i + 1] = T.seg_begin[i];
+            seg[3 * i + 2] = T.seg_end[i];
+        }
+    return TG_OK;
+}
+
+tg_status tg_plan_create(int64_t n_layers, const int64_t* offsets, int max_workers, tg_plan** out) {
+    if (out == nullptr) return TG_ERR_INVALID_ARG;
+    *out = nullptr;
+    const tg_status st = check_offsets(n_layers, offsets);
+    if (st != TG_OK) return st;
+    if (max_workers < 1) return TG_ERR_INVALID_ARG;
+    if (max_workers > TG_MAX_WORKERS) return TG_ERR_TOO_MANY_WORKERS;
+
+    Tables T;
+    tg_plan* p = nullptr;
+    try {
+        build_tables(n_layers, offsets, T);
+        p = new tg_plan();
+    } catch (const std::bad_alloc&) {
+        return TG_ERR_ALLOC;
+    }
+    p->n_layers = n_layers;
+    p->n = T.n;
+    p->packed_bytes = (((T.n + 3) / 4) + 15) / 16 * 16;
+    p->n_tiles = T.n_tiles;
+    p->n_chunks = T.n_chunks;
+    p->n_segs = (int64_t)T.seg_layer.size();
+    p->max_workers = max_workers;
+
+    const std::vector<int64_t> off(offsets, offsets + n_layers + 1);
+    const size_t np = (size_t)p->n_segs * (size_t)max_workers;
+    bool ok = upload(&p->d_off, off) && upload(&p->d_tile_layer, T.tile_layer) &&
+              upload(&p->d_chunk_seg, T.chunk_seg) && upload(&p->d_seg_layer, T.seg_layer) &&
+              upload(&p->d_seg_begin, T.seg_begin) && upload(&p->d_seg_end, T.seg_end) &&
+              upload(&p->d_layer_seg, T.layer_seg) &&
+              hip_ok(hipMalloc((void**)&p->d_psum, np * sizeof(double))) &&
+              hip_ok(hipMalloc((void**)&p->d_psq, np * sizeof(double))) &&
+              hip_ok(hipMalloc((void**)&p->d_pmax, np * sizeof(float)));
+    if (!ok) {
+        const bool oom = g_last_hip_error == (int)hipErrorOutOfMemory;
+        tg_plan_destroy(p);
+        return oom ? TG_ERR_ALLOC : TG_ERR_HIP;
+    }
+    *out = p;
+    return TG_OK;
+}
+
+tg_status tg_plan_destroy(tg_plan* p) {
+    if (p == nullptr) return TG_OK;
+    void* bufs[] = {p->d_off, p->d_tile_layer, p->d_chunk_seg, p->d_seg_layer, p->d_seg_begin,
+                    p->d_seg_end, p->d_layer_seg, p->d_psum, p->d_psq, p->d_pmax};
+    bool ok = true;
+    for (void* b : bufs)
+        if (b != nullptr) ok = hip_ok(hipFree(b)) && ok;
+    delete p;
+    return ok ? TG_OK : TG_ERR_HIP;
+}
+
+int64_t tg_num_elements(const tg_plan* p) { return p ? p->n : -1; }
+int64_t tg_num_layers(const tg_plan* p) { return p ? p->n_layers : -1; }
+int64_t tg_packed_bytes(const tg_plan* p) { return p ? p->packed_bytes : -1; }
+
+static tg_status check_workers(const tg_plan* p, int n_workers) {
+    if (p == nullptr || n_workers < 1) return TG_ERR_INVALID_ARG;
+    if (n_workers > p->max_workers || n_workers > TG_MAX_WORKERS) return TG_ERR_TOO_MANY_WORKERS;
+    return TG_OK;
+}
+
+tg_status tg_clip_stats(tg_plan* p, int n_workers, const float* const* grads, float c,
+                        float* tau, float* s_local, void* stream) {
+    tg_status st = check_workers(p, n_workers);
+    if (st != TG_OK) return st;
+    if (grads == nullptr || tau == nullptr || s_local == nullptr || std::isnan(c)) return TG_ERR_INVALID_ARG;
+    tg::StatsArgs a{};
+    for (int w = 0; w < n_workers; ++w) {
+        if (grads[w] == nullptr) return TG_ERR_INVALID_ARG;
+        if (!aligned(grads[w], 16)) return TG_ERR_ALIGNMENT;
+        a.grads[w] = grads[w];
+    }
+    if (!aligned(tau, 4) || !aligned(s_local, 4)) return TG_ERR_ALIGNMENT;
+    a.off = p->d_off;
+    a.chunk_seg = p->d_chunk_seg;
+    a.seg_layer = p->d_seg_layer;
+    a.seg_begin = p->d_seg_begin;
+    a.seg_end = p->d_seg_end;
+    a.psum = p->d_psum;
+    a.psq = p->d_psq;
+    a.pmax = p->d_pmax;
+    a.n_segs = p->n_segs;
+    hipStream_t s = (hipStream_t)stream;
+    hipLaunchKernelGGL(tg::clip_stats_partial_kernel, dim3((unsigned)p->n_chunks, (unsigned)n_workers),
+                       dim3(tg::kBlock), 0, s, a);
+    if (!hip_ok(hipGetLastError())) return TG_ERR_HIP;
+
+    tg::StatsFinalArgs f{};
+    f.off = p->d_off;
+    f.layer_seg = p->d_layer_seg;
+    f.psum = p->d_psum;
+    f.psq = p->d_psq;
+    f.pmax = p->d_pmax;
+    f.tau = tau;
+    f.s_local = s_local;
+    f.n_segs = p->n_segs;
+    f.n_layers = (int32_t)p->n_layers;
+    f.c = c;
+    f.noclip = (!(c > 0.0f) || std::isinf(c)) ? 1 : 0;
+    hipLaunchKernelGGL(tg::clip_stats_final_kernel, dim3((unsigned)p->n_layers, (unsigned)n_workers),
+                       dim3(tg::kBlock), 0, s, f);
+    if (!hip_ok(hipGetLastError())) return TG_ERR_HIP;
+    return TG_OK;
+}
+
+tg_status tg_share_scalers(tg_plan* p, int n_workers, const float* s_local, float* s_shared, void* stream) {
+    tg_status st = check_workers(p, n_workers);
+    if (st != TG_OK) return st;
+    if (s_local == nullptr || s_shared == nullptr) return TG_ERR_INVALID_ARG;
+    if (!aligned(s_local, 4) || !aligned(s_shared, 4)) return TG_ERR_ALIGNMENT;
+    const int L = (int)p->n_layers;
+    hipLaunchKernelGGL(tg::share_scalers_kernel, dim3((unsigned)((L + 255) / 256)), dim3(256), 0,
+                       (hipStream_t)stream, s_local, s_shared, n_workers, L);
+    if (!hip_ok(hipGetLastError())) return TG_ERR_HIP;
+    return TG_OK;
+}
+
+tg_status tg_ternarize_pack(tg_plan* p, int n_workers, uint32_t worker_base,
+                            const float* const* grads, const float* tau, const float* s_shared,
+                            uint64_t seed, uint32_t step, uint8_t* const* codes, void* stream) {
+    tg_status st = check_workers(p, n_workers);
+    if (st != TG_OK) return st;
+    if (grads == nullptr || codes == nullptr || tau == nullptr || s_shared == nullptr) return TG_ERR_INVALID_ARG;
+    tg::TernArgs a{};
+    for (int w = 0; w < n_workers; ++w) {
+        if (grads[w] == nullptr || codes[w] == nullptr) return TG_ERR_INVALID_ARG;
+        if (!aligned(grads[w], 16) || !aligned(codes[w], 4)) return TG_ERR_ALIGNMENT;
+        a.grads[w] = grads[w];
+        a.codes[w] = codes[w];
+    }
+    if (!aligned(tau, 4) || !aligned(s_shared, 4)) return TG_ERR_ALIGNMENT;
+    a.tau = tau;
+    a.s_shared = s_shared;
+    a.off = p->d_off;
+    a.tile_layer = p->d_tile_layer;
+    a.n = p->n;
+    a.packed_bytes = p->packed_bytes;
+    a.n_wave_tiles = (p->packed_bytes * 4 + tg::kWaveTile - 1) / tg::kWaveTile;
+    a.n_layers = (int32_t)p->n_layers;
+    a.key0 = (uint32_t)seed;
+    a.key1 = (uint32_t)(seed >> 32);
+    a.step = step;
+    a.worker_base = worker_base;
+    a.tiles_per_wave = 1;
+    const int64_t waves = (a.n_wave_tiles + a.tiles_per_wave - 1) / a.tiles_per_wave;
+    const int64_t blocks = (waves + tg::kBlock / tg::kWave - 1) / (tg::kBlock / tg::kWave);
+    hipLaunchKernelGGL(tg::ternarize_pack_kernel, dim3((unsigned)blocks, (unsigned)n_workers),
+                       dim3(tg::kBlock), 0, (hipStream_t)stream, a);
+    if (!hip_ok(hipGetLastError())) return TG_ERR_HIP;
+    return TG_OK;
+}
+
+tg_status tg_unpack_average(tg_plan* p, int n_workers, const uint8_t* const* codes,
+                            const float* s_shared, float* avg, void* stream) {
+    tg_status st = check_workers(p, n_workers);
+    if (st != TG_OK) return st;
+    if (codes == nullptr || s_shared == nullptr || avg == nullptr) return TG_ERR_INVALID_ARG;
+    tg::UnpackArgs a{};
+    for (int w = 0; w < n_workers; ++w) {
+        if (codes[w] == nullptr) return TG_ERR_INVALID_ARG;
+        if (!aligned(codes[w], 4)) return TG_ERR_ALIGNMENT;
+        a.codes[w] = codes[w];
+    }
+    if (!aligned(s_shared, 4) || !aligned(avg, 16)) return TG_ERR_ALIGNMENT;
+    a.s_shared = s_shared;
+    a.off = p->d_off;
+    a.tile_layer = p->d_tile_layer;
+    a.avg = avg;
+    a.n = p->n;
+    a.n_wave_tiles = (p->n + tg::kWaveTile - 1) / tg::kWaveTile;
+    a.packed_bytes = p->packed_bytes;
+    a.n_layers = (int32_t)p->n_layers;
+    a.n_workers = n_workers;
+    a.tiles_per_wave = 1;
+    const int64_t waves = (a.n_wave_tiles + a.tiles_per_wave - 1) / a.tiles_per_wave;
+    const int64_t blocks = (waves + tg::kBlock / tg::kWave - 1) / (tg::kBlock / tg::kWave);
+    hipLaunchKernelGGL(tg::unpack_average_kernel<false>, dim3((unsigned)blocks), dim3(tg::kBlock), 0,
+                       (hipStream_t)stream, a);
+    if (!hip_ok(hipGetLastError())) return TG_ERR_HIP;
+    return TG_OK;
+}
+
+}  // extern "C"

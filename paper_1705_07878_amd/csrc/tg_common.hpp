@@ -1,0 +1,58 @@
+// Shared device-side pieces of the TernGrad kernels (gfx950, wave64).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace tg {
+
+constexpr int kWave = 64;             // CDNA wavefront
+constexpr int kBlock = 256;           // 4 waves per workgroup
+constexpr int kWaveTile = 1024;       // elements one wave handles per step: 64 lanes x 4 x float4
+constexpr int kTileShift = 12;        // tile_layer[] granularity: 4096 elements
+constexpr int kMaxWorkers = 64;
+
+// Philox4x32 (Salmon et al., SC'11), published multipliers and key increments.
+constexpr uint32_t kPhiloxM0 = 0xD2511F53u;
+constexpr uint32_t kPhiloxM1 = 0xCD9E8D57u;
+constexpr uint32_t kPhiloxW0 = 0x9E3779B9u;
+constexpr uint32_t kPhiloxW1 = 0xBB67AE85u;
+
+struct U4 {
+    uint32_t x, y, z, w;
+};
+
+// Ten rounds over counter (c0,c1,c2,c3) under key (k0,k1).  The key schedule is
+// wave-uniform (it depends on the seed alone) and ends up in scalar registers.
+__device__ __forceinline__ U4 philox4x32_10(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3,
+                                            uint32_t k0, uint32_t k1) {
+#pragma unroll
+    for (int r = 0; r < 10; ++r) {
+        const uint64_t p0 = (uint64_t)kPhiloxM0 * c0;
+        const uint64_t p1 = (uint64_t)kPhiloxM1 * c2;
+        const uint32_t n0 = (uint32_t)(p1 >> 32) ^ c1 ^ k0;
+        const uint32_t n2 = (uint32_t)(p0 >> 32) ^ c3 ^ k1;
+        c1 = (uint32_t)p1;
+        c3 = (uint32_t)p0;
+        c0 = n0;
+        c2 = n2;
+        k0 += kPhiloxW0;
+        k1 += kPhiloxW1;
+    }
+    return U4{c0, c1, c2, c3};
+}
+
+// value held by the neighbouring lane (lane ^ 1), via DPP quad_perm [1,0,3,2]
+__device__ __forceinline__ uint32_t swap_adjacent(uint32_t v) {
+    return (uint32_t)__builtin_amdgcn_mov_dpp((int)v, 0xB1, 0xF, 0xF, true);
+}
+
+__device__ __forceinline__ int wave_uniform(int v) { return __builtin_amdgcn_readfirstlane(v); }
+
+// layer that holds flat element e, walking up from a layer known not to be past it
+__device__ __forceinline__ int layer_from(const int64_t* __restrict__ off, int n_layers, int l, int64_t e) {
+    while (l + 1 < n_layers && e >= off[l + 1]) ++l;
+    return l;
+}
+
+}  // namespace tg

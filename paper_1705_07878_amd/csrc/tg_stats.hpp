@@ -1,0 +1,193 @@
+// Per-layer clip threshold and scaler (Eq. 5 and Eq. 2) in one read of g.
+//
+// max|clip(g)| = min(max|g|, c*sigma), so sigma and the scaler come out of the
+// same pass.  Sums are fp64 and taken about a per-layer pivot K = first element
+// of the layer (shifted-data variance: exact for a constant layer, insensitive to
+// a large mean).  No float atomics: every statistics chunk of 16384 elements is
+// cut into segments (one per layer it touches); a workgroup reduces each of its
+// segments in a fixed tree and writes one partial; a second small kernel folds
+// the partials of each layer in a fixed order.  Results are bit-identical from
+// run to run.
+#pragma once
+
+#include "tg_common.hpp"
+
+namespace tg {
+
+constexpr int kStatChunk = 16384;   // elements per workgroup: 256 threads x 16 float4
+
+struct StatsArgs {
+    const float* grads[kMaxWorkers];
+    const int64_t* off;             // [L+1]
+    const int64_t* chunk_seg;       // [n_chunks+1] first segment of each chunk
+    const int32_t* seg_layer;       // [n_segs]
+    const int64_t* seg_begin;       // [n_segs]
+    const int64_t* seg_end;         // [n_segs]
+    double* psum;                   // [W][n_segs] sum (g - K)
+    double* psq;                    // [W][n_segs] sum (g - K)^2
+    float* pmax;                    // [W][n_segs] max |g|
+    int64_t n_segs;
+};
+
+struct Acc {
+    double s1, s2;
+    float m;
+};
+
+__device__ __forceinline__ void acc_add(Acc& a, const float x, const double K) {
+    const double d = (double)x - K;
+    a.s1 += d;
+    a.s2 = __builtin_fma(d, d, a.s2);
+    a.m = fmaxf(a.m, fabsf(x));
+}
+
+__device__ __forceinline__ void acc_add4(Acc& a, const float4 v, const double K) {
+    acc_add(a, v.x, K);
+    acc_add(a, v.y, K);
+    acc_add(a, v.z, K);
+    acc_add(a, v.w, K);
+}
+
+// xor butterfly: every lane ends with the same bits (a + b == b + a at each step)
+__device__ __forceinline__ Acc wave_reduce(Acc a) {
+#pragma unroll
+    for (int o = 32; o >= 1; o >>= 1) {
+        a.s1 += __shfl_xor(a.s1, o, kWave);
+        a.s2 += __shfl_xor(a.s2, o, kWave);
+        a.m = fmaxf(a.m, __shfl_xor(a.m, o, kWave));
+    }
+    return a;
+}
+
+__global__ void __launch_bounds__(kBlock) clip_stats_partial_kernel(const StatsArgs p) {
+    __shared__ double sh1[kBlock / kWave], sh2[kBlock / kWave];
+    __shared__ float shm[kBlock / kWave];
+
+    const int w = blockIdx.y;
+    const float* __restrict__ g = p.grads[w];
+    const int t = threadIdx.x;
+    const int64_t chunk = blockIdx.x;
+    const int64_t sb = p.chunk_seg[chunk], se = p.chunk_seg[chunk + 1];
+
+    for (int64_t sg = sb; sg < se; ++sg) {
+        const int64_t b = p.seg_begin[sg], e = p.seg_end[sg];
+        const double K = (double)g[p.off[p.seg_layer[sg]]];
+        Acc a = {0.0, 0.0, 0.0f};
+        const int64_t b4 = (b + 3) & ~(int64_t)3;
+        const int64_t e4 = e & ~(int64_t)3;
+        if (b4 < e4) {
+            const float4* gp = reinterpret_cast<const float4*>(g + b4);
+            const int64_t nv = (e4 - b4) >> 2;
+            if (nv == kStatChunk / 4) {
+                // whole chunk: 16 loads per thread, four in flight at a time
+#pragma unroll
+                for (int j = 0; j < 16; j += 4) {
+                    const float4 v0 = gp[(j + 0) * kBlock + t], v1 = gp[(j + 1) * kBlock + t];
+                    const float4 v2 = gp[(j + 2) * kBlock + t], v3 = gp[(j + 3) * kBlock + t];
+                    acc_add4(a, v0, K);
+                    acc_add4(a, v1, K);
+                    acc_add4(a, v2, K);
+                    acc_add4(a, v3, K);
+                }
+            } else {
+                for (int64_t i = t; i < nv; i += kBlock) acc_add4(a, gp[i], K);
+            }
+            // ragged head and tail, at most 3 elements each
+            if (t < b4 - b) acc_add(a, g[b + t], K);
+            if (t < e - e4) acc_add(a, g[e4 + t], K);
+        } else {
+            for (int64_t i = b + t; i < e; i += kBlock) acc_add(a, g[i], K);
+        }
+        a = wave_reduce(a);
+        const int wave = t >> 6;
+        if ((t & 63) == 0) {
+            sh1[wave] = a.s1;
+            sh2[wave] = a.s2;
+            shm[wave] = a.m;
+        }
+        __syncthreads();
+        if (t == 0) {
+            double s1 = sh1[0], s2 = sh2[0];
+            float m = shm[0];
+#pragma unroll
+            for (int k = 1; k < kBlock / kWave; ++k) {
+                s1 += sh1[k];
+                s2 += sh2[k];
+                m = fmaxf(m, shm[k]);
+            }
+            const int64_t o = (int64_t)w * p.n_segs + sg;
+            p.psum[o] = s1;
+            p.psq[o] = s2;
+            p.pmax[o] = m;
+        }
+        __syncthreads();
+    }
+}
+
+struct StatsFinalArgs {
+    const int64_t* off;             // [L+1]
+    const int64_t* layer_seg;       // [L+1] first segment of each layer
+    const double* psum;
+    const double* psq;
+    const float* pmax;
+    float* tau;                     // [W][L]
+    float* s_local;                 // [W][L]
+    int64_t n_segs;
+    int32_t n_layers;
+    float c;
+    int32_t noclip;
+};
+
+__global__ void __launch_bounds__(kBlock) clip_stats_final_kernel(const StatsFinalArgs p) {
+    __shared__ double sh1[kBlock / kWave], sh2[kBlock / kWave];
+    __shared__ float shm[kBlock / kWave];
+
+    const int l = blockIdx.x, w = blockIdx.y, t = threadIdx.x;
+    const int64_t sb = p.layer_seg[l], se = p.layer_seg[l + 1];
+    const int64_t base = (int64_t)w * p.n_segs;
+    Acc a = {0.0, 0.0, 0.0f};
+    for (int64_t i = sb + t; i < se; i += kBlock) {
+        a.s1 += p.psum[base + i];
+        a.s2 += p.psq[base + i];
+        a.m = fmaxf(a.m, p.pmax[base + i]);
+    }
+    a = wave_reduce(a);
+    if ((t & 63) == 0) {
+        sh1[t >> 6] = a.s1;
+        sh2[t >> 6] = a.s2;
+        shm[t >> 6] = a.m;
+    }
+    __syncthreads();
+    if (t == 0) {
+        double s1 = sh1[0], s2 = sh2[0];
+        float m = shm[0];
+#pragma unroll
+        for (int k = 1; k < kBlock / kWave; ++k) {
+            s1 += sh1[k];
+            s2 += sh2[k];
+            m = fmaxf(m, shm[k]);
+        }
+        const int64_t cnt = p.off[l + 1] - p.off[l];
+        double sigma = 0.0;
+        if (cnt > 0) {
+            const double md = s1 / (double)cnt;                     // mean - K
+            const double var = s2 / (double)cnt - md * md;
+            sigma = var > 0.0 ? sqrt(var) : 0.0;
+        }
+        const float tau = p.noclip ? __builtin_inff() : (float)((double)p.c * sigma);
+        const int64_t o = (int64_t)w * p.n_layers + l;
+        p.tau[o] = tau;
+        p.s_local[o] = fminf(m, tau);                               // Eq. 2 on the clipped layer
+    }
+}
+
+__global__ void share_scalers_kernel(const float* __restrict__ s_local, float* __restrict__ s_shared,
+                                     const int n_workers, const int n_layers) {
+    const int l = blockIdx.x * blockDim.x + threadIdx.x;
+    if (l >= n_layers) return;
+    float m = s_local[l];
+    for (int w = 1; w < n_workers; ++w) m = fmaxf(m, s_local[(int64_t)w * n_layers + l]);
+    s_shared[l] = m;                                                // Eq. 4
+}
+
+}  // namespace tg

@@ -1,0 +1,144 @@
+// Fused clip -> Bernoulli -> sign -> 2-bit pack (Eq. 1, 3, 5 and the 2-bit
+// encoding of Section 3.1).  One wave turns 1024 consecutive gradients into
+// 256 bytes of codes per step:
+//   * four fully coalesced 128-bit loads per lane (lane l, load k reads
+//     elements 256k + 4l .. 4l+3 of the wave tile), nothing is re-read;
+//   * one Philox4x32-10 block yields the 16-bit fields of 8 consecutive
+//     elements, so lanes 2j and 2j+1 each compute one block (for elements
+//     8j..8j+7 of two consecutive 256-element quarters) and swap halves over DPP;
+//   * per element: fp32 threshold fma, clip-min, integer compare, two
+//     funnel shifts that push the "non-zero" and "negative" bits into the byte;
+//   * the four code bytes of a lane are transposed through 256 B of LDS per
+//     wave so that every lane stores one dword and the wave 256 contiguous bytes.
+#pragma once
+
+#include "tg_common.hpp"
+
+namespace tg {
+
+struct TernArgs {
+    const float* grads[kMaxWorkers];
+    uint8_t* codes[kMaxWorkers];
+    const float* tau;           // [W][L]
+    const float* s_shared;      // [L]
+    const int64_t* off;         // [L+1]
+    const int32_t* tile_layer;  // layer of element t << kTileShift
+    int64_t n;
+    int64_t n_wave_tiles;       // wave tiles that cover packed_bytes * 4 elements
+    int64_t packed_bytes;       // ceil(n/4) rounded up to 16
+    int32_t n_layers;
+    uint32_t key0, key1, step, worker_base;
+    int32_t tiles_per_wave;
+};
+
+// 8 code bits of 4 elements.  wa, wb: the two Philox words whose 16-bit halves
+// are the random fields of v.x, v.y (wa) and v.z, v.w (wb).
+// threshold fl((2r+1) * s17) is formed as fma(r, 2*s17, s17): same real value,
+// one rounding.  Both sides of the comparison are non-negative floats, so the
+// order of their bit patterns as integers is their order as numbers.
+__device__ __forceinline__ uint32_t encode4(const float4 v, const uint32_t wa, const uint32_t wb,
+                                            const float tau, const float s16, const float s17) {
+    const float g[4] = {v.x, v.y, v.z, v.w};
+    const uint32_t r[4] = {wa & 0xFFFFu, wa >> 16, wb & 0xFFFFu, wb >> 16};
+    uint32_t acc = 0;
+#pragma unroll
+    for (int i = 3; i >= 0; --i) {
+        const float thr = __builtin_fmaf((float)r[i], s16, s17);
+        const uint32_t gb = __float_as_uint(g[i]);
+        const uint32_t ab = min(gb & 0x7FFFFFFFu, __float_as_uint(tau));   // min(|g|, tau)
+        const uint32_t d = __float_as_uint(thr) - ab;                       // bit 31 <=> thr < a
+        acc = __builtin_amdgcn_alignbit(acc, d & gb, 31);                   // push "negative"
+        acc = __builtin_amdgcn_alignbit(acc, d, 31);                        // push "non-zero"
+    }
+    return acc;   // code of g[i] at bits 2i..2i+1: 00 / 01 / 11
+}
+
+__global__ void __launch_bounds__(kBlock) ternarize_pack_kernel(const TernArgs p) {
+    __shared__ uint32_t lds[kBlock / kWave][kWave];   // 256 B per wave
+
+    const int w = blockIdx.y;
+    const float* __restrict__ g = p.grads[w];
+    uint8_t* __restrict__ codes = p.codes[w];
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wave = wave_uniform(threadIdx.x >> 6);
+    const uint32_t worker = p.worker_base + (uint32_t)w;
+    const int64_t first = ((int64_t)blockIdx.x * (kBlock / kWave) + wave) * p.tiles_per_wave;
+    const int par = lane & 1;
+
+    for (int it = 0; it < p.tiles_per_wave; ++it) {
+        const int64_t wt = first + it;
+        if (wt >= p.n_wave_tiles) break;
+        const int64_t e0 = wt * kWaveTile;
+        const int l0 = layer_from(p.off, p.n_layers, p.tile_layer[e0 >> kTileShift], e0);
+        const bool whole = (e0 + kWaveTile <= p.n) && (p.off[l0 + 1] >= e0 + kWaveTile);
+        uint32_t b[4];
+
+        if (whole) {
+            // ---- fast path: the tile lies inside layer l0 ----
+            const float4* gp = reinterpret_cast<const float4*>(g + e0) + lane;
+            const float4 v0 = gp[0], v1 = gp[64], v2 = gp[128], v3 = gp[192];
+            const float tau = p.tau[(int64_t)w * p.n_layers + l0];
+            const float s17 = p.s_shared[l0] * 0x1p-17f;
+            const float s16 = s17 * 2.0f;
+            // Philox blocks of this tile: q0 .. q0+127; lane computes q0 + 64P + 32*par + (lane>>1)
+            const uint64_t q = (uint64_t)(e0 >> 3) + (uint32_t)(32 * par + (lane >> 1));
+#pragma unroll
+            for (int P = 0; P < 2; ++P) {
+                const uint64_t qq = q + 64 * P;
+                const U4 R = philox4x32_10((uint32_t)qq, (uint32_t)(qq >> 32), worker, p.step, p.key0, p.key1);
+                // even lane keeps words 0,1 and sends 2,3; odd lane keeps 2,3 and sends 0,1
+                const uint32_t keep0 = par ? R.z : R.x, keep1 = par ? R.w : R.y;
+                const uint32_t recv0 = swap_adjacent(par ? R.x : R.z);
+                const uint32_t recv1 = swap_adjacent(par ? R.y : R.w);
+                const float4 va = P ? v2 : v0;   // quarter 2P
+                const float4 vb = P ? v3 : v1;   // quarter 2P+1
+                b[2 * P] = encode4(va, par ? recv0 : keep0, par ? recv1 : keep1, tau, s16, s17);
+                b[2 * P + 1] = encode4(vb, par ? keep0 : recv0, par ? keep1 : recv1, tau, s16, s17);
+            }
+        } else {
+            // ---- boundary path: layer changes inside the tile, or the tile is ragged ----
+#pragma unroll 1
+            for (int k = 0; k < 4; ++k) {
+                const int64_t e = e0 + 256 * k + 4 * lane;
+                uint32_t byte = 0;
+                if (e < p.n) {
+                    const uint64_t qq = (uint64_t)(e >> 3);
+                    const U4 R = philox4x32_10((uint32_t)qq, (uint32_t)(qq >> 32), worker, p.step, p.key0, p.key1);
+                    const uint32_t wa = (e & 4) ? R.z : R.x, wb = (e & 4) ? R.w : R.y;
+                    int l = l0;
+#pragma unroll 1
+                    for (int i = 0; i < 4; ++i) {
+                        if (e + i >= p.n) break;
+                        l = layer_from(p.off, p.n_layers, l, e + i);
+                        const float tau = p.tau[(int64_t)w * p.n_layers + l];
+                        const float s17 = p.s_shared[l] * 0x1p-17f;
+                        const float s16 = s17 * 2.0f;
+                        const uint32_t word = (i & 2) ? wb : wa;
+                        const uint32_t r = (i & 1) ? (word >> 16) : (word & 0xFFFFu);
+                        const float thr = __builtin_fmaf((float)r, s16, s17);
+                        const uint32_t gb = __float_as_uint(g[e + i]);
+                        const uint32_t ab = min(gb & 0x7FFFFFFFu, __float_as_uint(tau));
+                        const uint32_t d = __float_as_uint(thr) - ab;
+                        byte |= ((d >> 31) | (((d & gb) >> 31) << 1)) << (2 * i);
+                    }
+                }
+                b[k] = byte;
+            }
+        }
+
+        // ---- transpose bytes (position 64k + lane) into dwords (position 4*lane) ----
+        uint8_t* row = reinterpret_cast<uint8_t*>(lds[wave]);
+#pragma unroll
+        for (int k = 0; k < 4; ++k) row[64 * k + lane] = (uint8_t)b[k];
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        const uint32_t dw = lds[wave][lane];
+        const int64_t byte0 = (e0 >> 2) + 4 * lane;
+        if (byte0 < p.packed_bytes) *reinterpret_cast<uint32_t*>(codes + byte0) = dw;
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();   // the row is rewritten by the next step
+    }
+}
+
+}  // namespace tg

@@ -1,0 +1,163 @@
+// Fused unpack -> sum over workers -> rescale (Algorithm 1, server line, with
+// the shared scaler of Eq. 4).  One wave turns W x 256 bytes of codes into 1024
+// fp32 averages per step:
+//   * lane L loads one dword (16 codes) of every worker: 256 contiguous bytes
+//     per wave and worker;
+//   * the ternary values are summed in packed form, never one element at a
+//     time: code ^ 0b10 is t + 2 for the two's-complement code t, so one XOR
+//     biases all 16 fields of a dword; even and odd fields are spread into 4-bit
+//     counters, up to five workers are added per counter, then the counters are
+//     widened to bytes.  Byte sums start at 128 - 2W, so a final XOR with 0x80
+//     leaves k = sum_w t_w as a signed byte;
+//   * the signed bytes (1 B per element) are transposed through 1 KiB of LDS
+//     per wave so that every lane converts and stores whole float4s and the
+//     wave writes 1 KiB contiguous per store instruction.
+#pragma once
+
+#include "tg_common.hpp"
+
+namespace tg {
+
+struct UnpackArgs {
+    const uint8_t* codes[kMaxWorkers];
+    const float* s_shared;      // [L]
+    const int64_t* off;         // [L+1]
+    const int32_t* tile_layer;
+    float* avg;                 // [n]
+    int64_t n;
+    int64_t n_wave_tiles;       // ceil(n / 1024)
+    int64_t packed_bytes;
+    int32_t n_layers;
+    int32_t n_workers;
+    int32_t tiles_per_wave;
+};
+
+struct Nib {
+    uint32_t even, odd;         // 4-bit counters: nibble j of even/odd = element 2j / 2j+1
+};
+
+__device__ __forceinline__ void nib_add(Nib& a, const uint32_t x) {
+    const uint32_t y = x ^ 0xAAAAAAAAu;                 // every 2-bit field: t -> t + 2
+    a.even += y & 0x33333333u;
+    a.odd += (y >> 2) & 0x33333333u;
+}
+
+// 8-bit counters, byte m of e_lo / o_lo / e_hi / o_hi = element 4m / 4m+1 / 4m+2 / 4m+3
+struct Byt {
+    uint32_t e_lo, o_lo, e_hi, o_hi;
+};
+
+__device__ __forceinline__ void widen_add(Byt& b, const Nib a) {
+    b.e_lo += a.even & 0x0F0F0F0Fu;
+    b.e_hi += (a.even >> 4) & 0x0F0F0F0Fu;
+    b.o_lo += a.odd & 0x0F0F0F0Fu;
+    b.o_hi += (a.odd >> 4) & 0x0F0F0F0Fu;
+}
+
+// 4x4 byte transpose: D[m] = bytes of elements 4m, 4m+1, 4m+2, 4m+3
+__device__ __forceinline__ void gather_bytes(uint32_t D[4], const Byt b) {
+    const uint32_t p01_lo = __builtin_amdgcn_perm(b.o_lo, b.e_lo, 0x05010400u);   // el 0 1 4 5
+    const uint32_t p01_hi = __builtin_amdgcn_perm(b.o_lo, b.e_lo, 0x07030602u);   // el 8 9 12 13
+    const uint32_t p23_lo = __builtin_amdgcn_perm(b.o_hi, b.e_hi, 0x05010400u);   // el 2 3 6 7
+    const uint32_t p23_hi = __builtin_amdgcn_perm(b.o_hi, b.e_hi, 0x07030602u);   // el 10 11 14 15
+    D[0] = __builtin_amdgcn_perm(p23_lo, p01_lo, 0x05040100u);
+    D[1] = __builtin_amdgcn_perm(p23_lo, p01_lo, 0x07060302u);
+    D[2] = __builtin_amdgcn_perm(p23_hi, p01_hi, 0x05040100u);
+    D[3] = __builtin_amdgcn_perm(p23_hi, p01_hi, 0x07060302u);
+}
+
+// float4 of averages from 4 signed bytes
+__device__ __forceinline__ float4 scale4(const uint32_t d, const float sc) {
+    const int v = (int)d;
+    float4 o;
+    o.x = (float)(int)(int8_t)(v) * sc;
+    o.y = (float)(int)(int8_t)(v >> 8) * sc;
+    o.z = (float)(int)(int8_t)(v >> 16) * sc;
+    o.w = (float)(v >> 24) * sc;
+    return o;
+}
+
+template <bool NT>
+__device__ __forceinline__ void store4(float* dst, const float4 v) {
+    if (NT) {
+        __builtin_nontemporal_store(v.x, dst);
+        __builtin_nontemporal_store(v.y, dst + 1);
+        __builtin_nontemporal_store(v.z, dst + 2);
+        __builtin_nontemporal_store(v.w, dst + 3);
+    } else {
+        *reinterpret_cast<float4*>(dst) = v;
+    }
+}
+
+template <bool NT>
+__global__ void __launch_bounds__(kBlock) unpack_average_kernel(const UnpackArgs p) {
+    __shared__ uint32_t lds[kBlock / kWave][kWaveTile / 4];   // 1 KiB per wave
+
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wave = wave_uniform(threadIdx.x >> 6);
+    const int W = p.n_workers;
+    const float fW = (float)W;
+    const int64_t first = ((int64_t)blockIdx.x * (kBlock / kWave) + wave) * p.tiles_per_wave;
+    const uint32_t bias = (uint32_t)(128 - 2 * W) * 0x01010101u;
+
+    for (int it = 0; it < p.tiles_per_wave; ++it) {
+        const int64_t wt = first + it;
+        if (wt >= p.n_wave_tiles) break;
+        const int64_t e0 = wt * kWaveTile;
+        const int64_t byte0 = (e0 >> 2) + 4 * lane;
+        const bool in_codes = byte0 < p.packed_bytes;      // false only in the ragged last tile
+
+        Byt acc = {bias, bias, bias, bias};
+        for (int w0 = 0; w0 < W; w0 += 5) {
+            // up to five workers per 4-bit counter: 5 * 3 = 15
+            uint32_t x[5];
+#pragma unroll
+            for (int j = 0; j < 5; ++j) {
+                x[j] = 0xAAAAAAAAu;                         // an absent worker adds t + 2 = 0
+                if (w0 + j < W && in_codes)
+                    x[j] = *reinterpret_cast<const uint32_t*>(p.codes[w0 + j] + byte0);
+            }
+            Nib a = {0u, 0u};
+#pragma unroll
+            for (int j = 0; j < 5; ++j) nib_add(a, x[j]);
+            widen_add(acc, a);
+        }
+        // counters hold 128 + k: flip bit 7 to get k as int8
+        acc.e_lo ^= 0x80808080u; acc.o_lo ^= 0x80808080u; acc.e_hi ^= 0x80808080u; acc.o_hi ^= 0x80808080u;
+        uint32_t D[4];
+        gather_bytes(D, acc);
+
+        uint32_t* row = lds[wave];
+        *reinterpret_cast<uint4*>(row + 4 * lane) = make_uint4(D[0], D[1], D[2], D[3]);
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+
+        const int l0 = layer_from(p.off, p.n_layers, p.tile_layer[e0 >> kTileShift], e0);
+        const bool whole = (e0 + kWaveTile <= p.n) && (p.off[l0 + 1] >= e0 + kWaveTile);
+        if (whole) {
+            const float sc = p.s_shared[l0] / fW;
+            float* dst = p.avg + e0 + 4 * lane;
+#pragma unroll
+            for (int k = 0; k < 4; ++k) store4<NT>(dst + 256 * k, scale4(row[64 * k + lane], sc));
+        } else {
+#pragma unroll 1
+            for (int k = 0; k < 4; ++k) {
+                const int64_t e = e0 + 256 * k + 4 * lane;
+                const uint32_t d = row[64 * k + lane];
+                int l = l0;
+#pragma unroll 1
+                for (int i = 0; i < 4; ++i) {
+                    if (e + i >= p.n) break;
+                    l = layer_from(p.off, p.n_layers, l, e + i);
+                    const float sc = p.s_shared[l] / fW;
+                    p.avg[e + i] = (float)(int)(int8_t)(d >> (8 * i)) * sc;
+                }
+            }
+        }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();   // the row is rewritten by the next step
+    }
+}
+
+}  // namespace tg

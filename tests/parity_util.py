@@ -1,0 +1,117 @@
+"""Shared helpers of the GPU parity tests: run the HIP path through the C ABI
+and compare it with the CPU oracle on the same inputs.
+
+Protocol: (i) tau / s_local / s_shared within 1e-6 relative (absolute floor
+1e-6 * max|g| of the layer, for layers whose sigma is 0 or nearly so);
+(ii) the ORACLE's tau and s_shared are fed to both sides, then code buffers are
+compared byte for byte; (iii) the same codes and scaler go to both decoders,
+averages within 1e-6 relative and zeros exact.
+"""
+import numpy as np
+import torch
+
+REL = 1e-6
+
+
+def dev(a, dtype=None):
+    t = torch.as_tensor(np.ascontiguousarray(a))
+    if dtype is not None:
+        t = t.to(dtype)
+    return t.cuda()
+
+
+def gpu_clip_stats(plan, grads_dev, c):
+    W, L = len(grads_dev), plan.n_layers
+    tau = torch.full((W, L), float("nan"), dtype=torch.float32, device="cuda")
+    s_local = torch.full((W, L), float("nan"), dtype=torch.float32, device="cuda")
+    plan.tg_clip_stats(grads_dev, c, tau, s_local)
+    torch.cuda.synchronize()
+    return tau.cpu().numpy(), s_local.cpu().numpy()
+
+
+def gpu_share(plan, s_local):
+    W, L = s_local.shape
+    out = torch.full((L,), float("nan"), dtype=torch.float32, device="cuda")
+    plan.tg_share_scalers(W, dev(s_local), out)
+    torch.cuda.synchronize()
+    return out.cpu().numpy()
+
+
+def gpu_ternarize(plan, grads_dev, tau, s_shared, seed, step, worker_base=0):
+    W = len(grads_dev)
+    codes = [torch.full((plan.packed_bytes,), 0xCD, dtype=torch.uint8, device="cuda") for _ in range(W)]
+    plan.tg_ternarize_pack(grads_dev, dev(tau), dev(s_shared), seed, step, codes, worker_base=worker_base)
+    torch.cuda.synchronize()
+    return [c.cpu().numpy() for c in codes]
+
+
+def gpu_unpack_average(plan, codes_np, s_shared):
+    pb = plan.packed_bytes
+    cd = []
+    for c in codes_np:
+        buf = np.zeros(pb, np.uint8)
+        buf[:c.size] = c
+        cd.append(dev(buf))
+    avg = torch.full((plan.n,), float("nan"), dtype=torch.float32, device="cuda")
+    plan.tg_unpack_average(cd, dev(s_shared), avg)
+    torch.cuda.synchronize()
+    return avg.cpu().numpy()
+
+
+def assert_stats_close(got, want, grads_np, off, what):
+    got = np.asarray(got, np.float64)
+    want = np.asarray(want, np.float64)
+    for w in range(want.shape[0]):
+        for l in range(want.shape[1]):
+            a, b = got[w, l], want[w, l]
+            if np.isinf(b):
+                assert a == b, (what, w, l, a, b)
+                continue
+            seg = grads_np[w][off[l]:off[l + 1]]
+            floor = REL * float(np.abs(seg).max()) if seg.size else 0.0
+            assert abs(a - b) <= max(REL * abs(b), floor), (what, w, l, a, b)
+
+
+def assert_avg_close(got, want):
+    assert got.shape == want.shape
+    zero = want == 0
+    assert np.all(got[zero] == 0), "zeros of the average must be exact"
+    err = np.abs(got.astype(np.float64) - want.astype(np.float64))
+    assert np.all(err <= REL * np.abs(want.astype(np.float64))), float((err / np.maximum(np.abs(want), 1e-300)).max())
+
+
+def full_parity(oracle, binding, off, grads_np, c=2.5, seed=0, step=0, worker_base=0):
+    """All four calls against the oracle on one input set. Returns what the oracle computed."""
+    off = np.asarray(off, np.int64)
+    W = len(grads_np)
+    n = int(off[-1])
+    plan = binding.Plan(off, W)
+    try:
+        assert plan.n == n and plan.n_layers == off.size - 1
+        assert plan.packed_bytes == ((n + 3) // 4 + 15) // 16 * 16
+        gd = [dev(g) for g in grads_np]
+        # (i) statistics
+        o_tau, o_sloc = zip(*[oracle.clip_stats(g, off, c) for g in grads_np])
+        o_tau, o_sloc = np.stack(o_tau), np.stack(o_sloc)
+        g_tau, g_sloc = gpu_clip_stats(plan, gd, c)
+        assert_stats_close(g_tau, o_tau, grads_np, off, "tau")
+        assert_stats_close(g_sloc, o_sloc, grads_np, off, "s_local")
+        # Eq. 4 is exact
+        o_s = oracle.share_scalers(o_sloc)
+        assert np.array_equal(gpu_share(plan, o_sloc), o_s)
+        # (ii) codes, fed the oracle's tau and s
+        o_codes = [oracle.ternarize_pack(g, off, o_tau[w], o_s, seed, step, worker_base + w)
+                   for w, g in enumerate(grads_np)]
+        g_codes = gpu_ternarize(plan, gd, o_tau, o_s, seed, step, worker_base)
+        nb = (n + 3) // 4
+        for w in range(W):
+            assert np.array_equal(g_codes[w][:nb], o_codes[w]), ("codes differ", w,
+                                                                   int(np.flatnonzero(g_codes[w][:nb] != o_codes[w])[0]))
+            assert not g_codes[w][nb:].any(), "padding bytes must be 0"
+        # (iii) averages from the same codes and scaler
+        o_avg = oracle.unpack_average(o_codes, off, o_s)
+        g_avg = gpu_unpack_average(plan, o_codes, o_s)
+        assert_avg_close(g_avg, o_avg)
+        return dict(tau=o_tau, s_local=o_sloc, s_shared=o_s, codes=o_codes, avg=o_avg)
+    finally:
+        plan.close()

@@ -1,0 +1,112 @@
+"""No-GPU checks of the C ABI: the library loads, exports every symbol the
+header declares, rejects bad arguments before touching a device, and derives
+the right tables from an offset table."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def binding():
+    from paper_1705_07878_amd import build
+    build.build(force=False, verbose=False)
+    from paper_1705_07878_amd import binding as b
+    return b
+
+
+def test_every_declared_symbol_is_exported(binding):
+    hdr = open(os.path.join(ROOT, "include", "terngrad.h")).read()
+    hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
+    names = set(re.findall(r"\b(tg_[a-z_0-9]+)\s*\(", hdr))
+    assert {"tg_clip_stats", "tg_share_scalers", "tg_ternarize_pack", "tg_unpack_average",
+            "tg_plan_create", "tg_plan_destroy"} <= names
+    for name in names:
+        assert hasattr(binding.lib, name), name
+
+
+def test_strerror_and_status_values(binding):
+    assert binding.tg_strerror(0) == "ok"
+    for st in (-1, -2, -3, -4, -5):
+        assert binding.tg_strerror(st) not in ("ok", "unknown status")
+    assert binding.tg_strerror(-99) == "unknown status"
+    hdr = open(os.path.join(ROOT, "include", "terngrad.h")).read()
+    assert int(re.search(r"#define TG_MAX_WORKERS (\d+)", hdr).group(1)) == binding.TG_MAX_WORKERS
+
+
+def _create(binding, off, max_workers=2):
+    off = np.asarray(off, np.int64)
+    h = ctypes.c_void_p()
+    st = binding.lib.tg_plan_create(off.size - 1, off.ctypes.data_as(ctypes.POINTER(ctypes.c_int64)),
+                                    max_workers, ctypes.byref(h))
+    return st, h
+
+
+def test_plan_create_rejects_bad_tables_before_any_device_call(binding):
+    assert _create(binding, [1, 5])[0] == binding.TG_ERR_INVALID_ARG          # off[0] != 0
+    assert _create(binding, [0, 5, 3])[0] == binding.TG_ERR_INVALID_ARG       # not monotone
+    assert _create(binding, [0, 0])[0] == binding.TG_ERR_INVALID_ARG          # n = 0
+    assert _create(binding, [0, 8], 0)[0] == binding.TG_ERR_INVALID_ARG
+    assert _create(binding, [0, 8], 65)[0] == binding.TG_ERR_TOO_MANY_WORKERS
+    st = binding.lib.tg_plan_create(1, None, 1, ctypes.byref(ctypes.c_void_p()))
+    assert st == binding.TG_ERR_INVALID_ARG
+    st = binding.lib.tg_plan_create(1, (ctypes.c_int64 * 2)(0, 8), 1, None)
+    assert st == binding.TG_ERR_INVALID_ARG
+
+
+def test_null_plan_is_rejected(binding):
+    assert binding.lib.tg_plan_destroy(None) == binding.TG_OK
+    assert binding.lib.tg_num_elements(None) == -1
+    assert binding.lib.tg_packed_bytes(None) == -1
+    assert binding.lib.tg_clip_stats(None, 1, None, 2.5, None, None, None) == binding.TG_ERR_INVALID_ARG
+    assert binding.lib.tg_share_scalers(None, 1, None, None, None) == binding.TG_ERR_INVALID_ARG
+    assert binding.lib.tg_ternarize_pack(None, 1, 0, None, None, None, 0, 0, None, None) == binding.TG_ERR_INVALID_ARG
+    assert binding.lib.tg_unpack_average(None, 1, None, None, None, None) == binding.TG_ERR_INVALID_ARG
+
+
+def _brute_tables(off, tile, chunk):
+    off = np.asarray(off, np.int64)
+    n = int(off[-1])
+    lay = np.repeat(np.arange(off.size - 1), np.diff(off))
+    tile_layer = lay[np.arange(0, n, tile)]
+    segs = []
+    for cb in range(0, n, chunk):
+        ce = min(n, cb + chunk)
+        e = cb
+        while e < ce:
+            l = lay[e]
+            end = min(int(off[l + 1]), ce)
+            segs.append((l, e, end))
+            e = end
+    return tile_layer, np.array(segs, np.int64).reshape(-1, 3)
+
+
+@pytest.mark.parametrize("sizes", [[1], [4096], [4097], [16384, 16384], [5, 0, 0, 20000, 1, 40000, 3],
+                                   [500, 20, 25000, 50, 400000, 500, 5000, 10], [0, 0, 7], [100000]])
+def test_tables_match_brute_force(binding, sizes):
+    off = np.concatenate([[0], np.cumsum(sizes)])
+    d = binding.tg_describe_tables(off)
+    tl, segs = _brute_tables(off, d["tile_elems"], d["chunk_elems"])
+    assert np.array_equal(d["tile_layer"], tl)
+    assert np.array_equal(d["segments"], segs)
+    # segments tile [0, n) exactly, in order, each inside one layer and one chunk
+    s = d["segments"]
+    assert s[0, 1] == 0 and s[-1, 2] == off[-1] and np.all(s[1:, 1] == s[:-1, 2]) and np.all(s[:, 2] > s[:, 1])
+
+
+def test_binding_refuses_to_import_without_the_library(tmp_path):
+    import subprocess
+    import sys
+    code = ("import importlib.util, sys\n"
+            "spec = importlib.util.spec_from_file_location('b', sys.argv[1])\n"
+            "m = importlib.util.module_from_spec(spec)\n"
+            "try:\n    spec.loader.exec_module(m)\nexcept ImportError as e:\n    print('IMPORTERROR', e)\n")
+    src = open(os.path.join(ROOT, "paper_1705_07878_amd", "binding.py")).read()
+    p = tmp_path / "binding.py"
+    p.write_text(src)
+    out = subprocess.run([sys.executable, "-c", code, str(p)], capture_output=True, text=True).stdout
+    assert "IMPORTERROR" in out and "not built" in out

@@ -1,0 +1,188 @@
+#!/usr/bin/env python3
+"""Benchmark of the TernGrad hot path on one MI355X.
+
+A "step" is one pass of the whole hot path over one batch of synthetic
+gradients: tg_clip_stats -> tg_share_scalers -> tg_ternarize_pack ->
+tg_unpack_average for all W simulated workers (W gradient buffers on the one
+device).  Inputs are resident in HBM before the timed region.  Prints ONE JSON
+line; `value` is fp32 gradient bytes consumed per second (W * n * 4 B / step).
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload alexnet]
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0   # MI355X published HBM3E bandwidth
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="alexnet",
+                    choices=["lenet", "alexnet", "googlenet_like", "vgg_a", "flat"])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    return ap.parse_args()
+
+
+def traffic_from_profile(kernel: str, workload: str):
+    """HBM bytes per launch of `kernel` from the committed rocprofv3 --pmc summary, or None."""
+    path = os.path.join(ROOT, "profiles", "%s_%s_pmc.txt" % (kernel, workload))
+    if not os.path.exists(path):
+        return None
+    for line in open(path):
+        if line.startswith("traffic_bytes_per_launch="):
+            return float(line.split("=", 1)[1])
+    return None
+
+
+def cpu_baseline(wl, grads_host, sample_note):
+    """The oracle as it stands, all host cores, same four calls over the W workers."""
+    import numpy as np
+    import oracle
+    cores = len(os.sched_getaffinity(0))
+    cores = min(cores, int(os.environ.get("OMP_NUM_THREADS", cores)))
+    used = oracle.set_threads(cores)
+    try:
+        off = wl.offsets
+        t0 = time.perf_counter()
+        st = [oracle.clip_stats(g, off, wl.clip_c) for g in grads_host]
+        tau = [s[0] for s in st]
+        s_shared = oracle.share_scalers(np.stack([s[1] for s in st]))
+        codes = [oracle.ternarize_pack(g, off, tau[w], s_shared, wl.seed, wl.step, w)
+                 for w, g in enumerate(grads_host)]
+        oracle.unpack_average(codes, off, s_shared)
+        dt = time.perf_counter() - t0
+    finally:
+        oracle.set_threads(1)
+    in_bytes = sum(g.size for g in grads_host) * 4.0
+    return {"value": in_bytes / dt / 1e9, "unit": "GB/s", "cores": used, "kind": "oracle",
+            "sample": sample_note, "seconds": dt}
+
+
+def main():
+    args = parse()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU only (the W workers are W gradient buffers on one "
+              "device; no collectives). Re-run with --gpus 1.", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from paper_1705_07878_amd import binding, workloads
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    wl = workloads.BY_NAME[args.workload]()
+    W, n, L = wl.n_workers, wl.n, wl.n_layers
+
+    grads = [workloads.make_gradient(wl, w, "cuda") for w in range(W)]
+    plan = binding.Plan(wl.offsets, W)
+    tau = torch.empty((W, L), dtype=torch.float32, device="cuda")
+    s_local = torch.empty((W, L), dtype=torch.float32, device="cuda")
+    s_shared = torch.empty((L,), dtype=torch.float32, device="cuda")
+    codes = [torch.empty((plan.packed_bytes,), dtype=torch.uint8, device="cuda") for _ in range(W)]
+    avg = torch.empty((n,), dtype=torch.float32, device="cuda")
+    stream = torch.cuda.current_stream()
+
+    def step(t, ev=None):
+        if ev: ev[0].record(stream)
+        plan.tg_clip_stats(grads, wl.clip_c, tau, s_local)
+        if ev: ev[1].record(stream)
+        plan.tg_share_scalers(W, s_local, s_shared)
+        if ev: ev[2].record(stream)
+        plan.tg_ternarize_pack(grads, tau, s_shared, wl.seed, wl.step + t, codes)
+        if ev: ev[3].record(stream)
+        plan.tg_unpack_average(codes, s_shared, avg)
+        if ev: ev[4].record(stream)
+
+    for t in range(args.warmup):
+        step(t)
+    torch.cuda.synchronize()
+
+    # whole-step timing: exactly K steps between two synchronisations
+    t0 = time.perf_counter()
+    for t in range(args.steps):
+        step(t)
+    torch.cuda.synchronize()
+    ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
+
+    # per-call timing with events on the launch stream, over K more steps
+    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(5)] for _ in range(args.steps)]
+    for t in range(args.steps):
+        step(t, evs[t])
+    torch.cuda.synchronize()
+    names = ["clip_stats", "share_scalers", "ternarize_pack", "unpack_average"]
+    call_ms = {nm: float(np.mean([e[i].elapsed_time(e[i + 1]) for e in evs])) for i, nm in enumerate(names)}
+
+    in_bytes = W * n * 4.0
+    alg_bytes = {"clip_stats": W * n * 4.0, "ternarize_pack": W * n * 4.25,
+                 "unpack_average": n * (4.0 + 0.25 * W)}
+    kern = {}
+    for nm in ("clip_stats", "ternarize_pack", "unpack_average"):
+        gbs = alg_bytes[nm] / (call_ms[nm] * 1e-3) / 1e9
+        kern[nm] = {"ms": round(call_ms[nm], 4), "algorithmic_GBps": round(gbs, 1),
+                    "pct_hbm_peak": round(100 * gbs / HBM_PEAK_GBS, 1)}
+    kern["ternarize_pack"]["fp32_in_GBps"] = round(in_bytes / (call_ms["ternarize_pack"] * 1e-3) / 1e9, 1)
+    kern["share_scalers"] = {"ms": round(call_ms["share_scalers"], 4)}
+
+    dom = "ternarize_pack"
+    achieved = alg_bytes[dom] / (call_ms[dom] * 1e-3) / 1e9
+    roofline = {"bound": "hbm", "kernel": "tg::ternarize_pack_kernel", "achieved": round(achieved, 1),
+                "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
+                "traffic": traffic_from_profile(dom, args.workload),
+                "algorithmic_bytes_per_launch": alg_bytes[dom], "avg_launch_ms": round(call_ms[dom], 4)}
+
+    out = {
+        "metric": "ternarize+pack and unpack-average GB/s (fp32 in) and % HBM peak; ms/step",
+        "value": round(in_bytes / (ms_per_step * 1e-3) / 1e9, 2), "unit": "GB/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32",
+        "data": "synthetic",
+        "config": {"workload": "%s gradients, fp32, W=%d simulated workers on one GPU, n=%d, L=%d, c=%.1f"
+                               % (wl.name, W, n, L, wl.clip_c)},
+        "kernels": kern, "roofline": roofline,
+    }
+
+    if not args.no_cpu_baseline:
+        # bounded sample: the whole workload if W*n <= 2.6e8 element passes, else its first layers
+        cap = 260_000_000 // W
+        if n <= cap:
+            sub, note = wl, "the whole step (4 calls, all %d workers) of this workload" % W
+            host = [g.cpu().numpy() for g in grads]
+        else:
+            sizes, tot = [], 0
+            for s in wl.layer_sizes:
+                take = min(s, cap - tot)
+                if take <= 0:
+                    break
+                sizes.append(take)
+                tot += take
+            sub = workloads.custom(sizes, W, name=wl.name + " (truncated)", clip_c=wl.clip_c, seed=wl.seed,
+                                   step=wl.step)
+            note = "the whole step on the first %d elements of each of the %d workers" % (tot, W)
+            host = [g[:tot].cpu().numpy() for g in grads]
+        out["cpu_baseline"] = cpu_baseline(sub, host, note)
+        out["cpu_baseline"]["value"] = round(out["cpu_baseline"]["value"], 3)
+        out["cpu_baseline"]["seconds"] = round(out["cpu_baseline"]["seconds"], 2)
+
+    # a plain copy of known size, outside the timed region: the calibration kernel for --pmc runs
+    cal_src = torch.empty(64 * 1024 * 1024, dtype=torch.float32, device="cuda").normal_()
+    cal_dst = torch.empty_like(cal_src)
+    cal_dst.copy_(cal_src)
+    torch.cuda.synchronize()
+
+    print(json.dumps(out))
+    plan.close()
+
+
+if __name__ == "__main__":
+    main()

@@ -329,7 +329,7 @@ tg_status tg_unpack_average(tg_plan* p, int n_workers, const uint8_t* const* cod
     a.tiles_per_wave = 1;
     const int64_t waves = (a.n_wave_tiles + a.tiles_per_wave - 1) / a.tiles_per_wave;
     const int64_t blocks = (waves + tg::kBlock / tg::kWave - 1) / (tg::kBlock / tg::kWave);
-    hipLaunchKernelGGL(tg::unpack_average_kernel<false>, dim3((unsigned)blocks), dim3(tg::kBlock), 0,
+    hipLaunchKernelGGL(tg::unpack_average_kernel<true>, dim3((unsigned)blocks), dim3(tg::kBlock), 0,
                        (hipStream_t)stream, a);
     if (!hip_ok(hipGetLastError())) return TG_ERR_HIP;
     return TG_OK;

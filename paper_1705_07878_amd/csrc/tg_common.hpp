@@ -22,6 +22,27 @@ struct U4 {
     uint32_t x, y, z, w;
 };
 
+// a ^ b ^ c in one instruction (v_bitop3_b32, truth table 0x96)
+__device__ __forceinline__ uint32_t xor3(uint32_t a, uint32_t b, uint32_t c) {
+    return __builtin_amdgcn_bitop3_b32(a, b, c, 0x96);
+}
+
+// min(|g|, tau) for tau >= 0 in one instruction.  fminf() would first canonicalise both
+// operands (two extra instructions); the hardware minimum already returns the right
+// value for every non-NaN input, denormals included.
+__device__ __forceinline__ float min_abs(float g, float tau) {
+    float r;
+    asm("v_min_f32 %0, |%1|, %2" : "=v"(r) : "v"(g), "v"(tau));
+    return r;
+}
+
+// max(m, |x|) in one instruction, same reasoning
+__device__ __forceinline__ float max_abs(float m, float x) {
+    float r;
+    asm("v_max_f32 %0, |%1|, %2" : "=v"(r) : "v"(x), "v"(m));
+    return r;
+}
+
 // Ten rounds over counter (c0,c1,c2,c3) under key (k0,k1).  The key schedule is
 // wave-uniform (it depends on the seed alone) and ends up in scalar registers.
 __device__ __forceinline__ U4 philox4x32_10(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3,
@@ -30,8 +51,8 @@ __device__ __forceinline__ U4 philox4x32_10(uint32_t c0, uint32_t c1, uint32_t c
     for (int r = 0; r < 10; ++r) {
         const uint64_t p0 = (uint64_t)kPhiloxM0 * c0;
         const uint64_t p1 = (uint64_t)kPhiloxM1 * c2;
-        const uint32_t n0 = (uint32_t)(p1 >> 32) ^ c1 ^ k0;
-        const uint32_t n2 = (uint32_t)(p0 >> 32) ^ c3 ^ k1;
+        const uint32_t n0 = xor3((uint32_t)(p1 >> 32), c1, k0);
+        const uint32_t n2 = xor3((uint32_t)(p0 >> 32), c3, k1);
         c1 = (uint32_t)p1;
         c3 = (uint32_t)p0;
         c0 = n0;

@@ -38,7 +38,7 @@ __device__ __forceinline__ void acc_add(Acc& a, const float x, const double K) {
     const double d = (double)x - K;
     a.s1 += d;
     a.s2 = __builtin_fma(d, d, a.s2);
-    a.m = fmaxf(a.m, fabsf(x));
+    a.m = max_abs(a.m, x);
 }
 
 __device__ __forceinline__ void acc_add4(Acc& a, const float4 v, const double K) {

@@ -45,7 +45,7 @@ __device__ __forceinline__ uint32_t encode4(const float4 v, const uint32_t wa, c
     for (int i = 3; i >= 0; --i) {
         const float thr = __builtin_fmaf((float)r[i], s16, s17);
         const uint32_t gb = __float_as_uint(g[i]);
-        const uint32_t ab = min(gb & 0x7FFFFFFFu, __float_as_uint(tau));   // min(|g|, tau)
+        const uint32_t ab = __float_as_uint(min_abs(g[i], tau));           // min(|g|, tau)
         const uint32_t d = __float_as_uint(thr) - ab;                       // bit 31 <=> thr < a
         acc = __builtin_amdgcn_alignbit(acc, d & gb, 31);                   // push "negative"
         acc = __builtin_amdgcn_alignbit(acc, d, 31);                        // push "non-zero"
@@ -86,14 +86,17 @@ __global__ void __launch_bounds__(kBlock) ternarize_pack_kernel(const TernArgs p
             for (int P = 0; P < 2; ++P) {
                 const uint64_t qq = q + 64 * P;
                 const U4 R = philox4x32_10((uint32_t)qq, (uint32_t)(qq >> 32), worker, p.step, p.key0, p.key1);
-                // even lane keeps words 0,1 and sends 2,3; odd lane keeps 2,3 and sends 0,1
-                const uint32_t keep0 = par ? R.z : R.x, keep1 = par ? R.w : R.y;
-                const uint32_t recv0 = swap_adjacent(par ? R.x : R.z);
-                const uint32_t recv1 = swap_adjacent(par ? R.y : R.w);
+                // quarter 2P: elements 8j..8j+7 belong to the even lane's block; the even lane
+                // uses its words 0,1, the odd lane the even lane's words 2,3.  Quarter 2P+1:
+                // the odd lane's block; the even lane takes its words 0,1, the odd lane keeps 2,3.
+                const uint32_t nx = swap_adjacent(R.x), ny = swap_adjacent(R.y);
+                const uint32_t nz = swap_adjacent(R.z), nw = swap_adjacent(R.w);
+                const uint32_t a0 = par ? nz : R.x, a1 = par ? nw : R.y;
+                const uint32_t b0 = par ? R.z : nx, b1 = par ? R.w : ny;
                 const float4 va = P ? v2 : v0;   // quarter 2P
                 const float4 vb = P ? v3 : v1;   // quarter 2P+1
-                b[2 * P] = encode4(va, par ? recv0 : keep0, par ? recv1 : keep1, tau, s16, s17);
-                b[2 * P + 1] = encode4(vb, par ? keep0 : recv0, par ? keep1 : recv1, tau, s16, s17);
+                b[2 * P] = encode4(va, a0, a1, tau, s16, s17);
+                b[2 * P + 1] = encode4(vb, b0, b1, tau, s16, s17);
             }
         } else {
             // ---- boundary path: layer changes inside the tile, or the tile is ragged ----
@@ -117,7 +120,7 @@ __global__ void __launch_bounds__(kBlock) ternarize_pack_kernel(const TernArgs p
                         const uint32_t r = (i & 1) ? (word >> 16) : (word & 0xFFFFu);
                         const float thr = __builtin_fmaf((float)r, s16, s17);
                         const uint32_t gb = __float_as_uint(g[e + i]);
-                        const uint32_t ab = min(gb & 0x7FFFFFFFu, __float_as_uint(tau));
+                        const uint32_t ab = __float_as_uint(min_abs(g[e + i], tau));
                         const uint32_t d = __float_as_uint(thr) - ab;
                         byte |= ((d >> 31) | (((d & gb) >> 31) << 1)) << (2 * i);
                     }

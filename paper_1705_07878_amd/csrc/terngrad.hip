@@ -296,9 +296,7 @@ tg_status tg_ternarize_pack(tg_plan* p, int n_workers, uint32_t worker_base,
     a.key1 = (uint32_t)(seed >> 32);
     a.step = step;
     a.worker_base = worker_base;
-    a.tiles_per_wave = 1;
-    const int64_t waves = (a.n_wave_tiles + a.tiles_per_wave - 1) / a.tiles_per_wave;
-    const int64_t blocks = (waves + tg::kBlock / tg::kWave - 1) / (tg::kBlock / tg::kWave);
+    const int64_t blocks = (a.n_wave_tiles + tg::kBlock / tg::kWave - 1) / (tg::kBlock / tg::kWave);
     hipLaunchKernelGGL(tg::ternarize_pack_kernel, dim3((unsigned)blocks, (unsigned)n_workers),
                        dim3(tg::kBlock), 0, (hipStream_t)stream, a);
     if (!hip_ok(hipGetLastError())) return TG_ERR_HIP;
@@ -326,9 +324,7 @@ tg_status tg_unpack_average(tg_plan* p, int n_workers, const uint8_t* const* cod
     a.packed_bytes = p->packed_bytes;
     a.n_layers = (int32_t)p->n_layers;
     a.n_workers = n_workers;
-    a.tiles_per_wave = 1;
-    const int64_t waves = (a.n_wave_tiles + a.tiles_per_wave - 1) / a.tiles_per_wave;
-    const int64_t blocks = (waves + tg::kBlock / tg::kWave - 1) / (tg::kBlock / tg::kWave);
+    const int64_t blocks = (a.n_wave_tiles + tg::kBlock / tg::kWave - 1) / (tg::kBlock / tg::kWave);
     hipLaunchKernelGGL(tg::unpack_average_kernel<true>, dim3((unsigned)blocks), dim3(tg::kBlock), 0,
                        (hipStream_t)stream, a);
     if (!hip_ok(hipGetLastError())) return TG_ERR_HIP;

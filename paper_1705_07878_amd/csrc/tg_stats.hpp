@@ -76,21 +76,21 @@ __global__ void __launch_bounds__(kBlock) clip_stats_partial_kernel(const StatsA
         const int64_t b4 = (b + 3) & ~(int64_t)3;
         const int64_t e4 = e & ~(int64_t)3;
         if (b4 < e4) {
-            const float4* gp = reinterpret_cast<const float4*>(g + b4);
             const int64_t nv = (e4 - b4) >> 2;
             if (nv == kStatChunk / 4) {
                 // whole chunk: 16 loads per thread, four in flight at a time
 #pragma unroll
                 for (int j = 0; j < 16; j += 4) {
-                    const float4 v0 = gp[(j + 0) * kBlock + t], v1 = gp[(j + 1) * kBlock + t];
-                    const float4 v2 = gp[(j + 2) * kBlock + t], v3 = gp[(j + 3) * kBlock + t];
+                    const float* q = g + b4 + 4 * ((int64_t)j * kBlock + t);
+                    const float4 v0 = load_stream(q), v1 = load_stream(q + 4 * kBlock);
+                    const float4 v2 = load_stream(q + 8 * kBlock), v3 = load_stream(q + 12 * kBlock);
                     acc_add4(a, v0, K);
                     acc_add4(a, v1, K);
                     acc_add4(a, v2, K);
                     acc_add4(a, v3, K);
                 }
             } else {
-                for (int64_t i = t; i < nv; i += kBlock) acc_add4(a, gp[i], K);
+                for (int64_t i = t; i < nv; i += kBlock) acc_add4(a, load_stream(g + b4 + 4 * i), K);
             }
             // ragged head and tail, at most 3 elements each
             if (t < b4 - b) acc_add(a, g[b + t], K);

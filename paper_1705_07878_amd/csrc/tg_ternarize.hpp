@@ -2,7 +2,8 @@
 // encoding of Section 3.1).  One wave turns 1024 consecutive gradients into
 // 256 bytes of codes per step:
 //   * four fully coalesced 128-bit loads per lane (lane l, load k reads
-//     elements 256k + 4l .. 4l+3 of the wave tile), nothing is re-read;
+//     elements 256k + 4l .. 4l+3 of the wave tile), issued before anything that
+//     depends on the layer tables, so table and data latencies overlap;
 //   * one Philox4x32-10 block yields the 16-bit fields of 8 consecutive
 //     elements, so lanes 2j and 2j+1 each compute one block (for elements
 //     8j..8j+7 of two consecutive 256-element quarters) and swap halves over DPP;
@@ -28,7 +29,6 @@ struct TernArgs {
     int64_t packed_bytes;       // ceil(n/4) rounded up to 16
     int32_t n_layers;
     uint32_t key0, key1, step, worker_base;
-    int32_t tiles_per_wave;
 };
 
 // 8 code bits of 4 elements.  wa, wb: the two Philox words whose 16-bit halves
@@ -62,24 +62,23 @@ __global__ void __launch_bounds__(kBlock) ternarize_pack_kernel(const TernArgs p
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = wave_uniform(threadIdx.x >> 6);
     const uint32_t worker = p.worker_base + (uint32_t)w;
-    const int64_t first = ((int64_t)blockIdx.x * (kBlock / kWave) + wave) * p.tiles_per_wave;
     const int par = lane & 1;
 
-    for (int it = 0; it < p.tiles_per_wave; ++it) {
-        const int64_t wt = first + it;
-        if (wt >= p.n_wave_tiles) break;
+    {
+        // one tile per wave: short-lived waves and a very large grid stream best here, and
+        // without a loop every table lookup below is a scalar load
+        const int64_t wt = (int64_t)blockIdx.x * (kBlock / kWave) + wave;
+        if (wt >= p.n_wave_tiles) return;
         const int64_t e0 = wt * kWaveTile;
-        const int l0 = layer_from(p.off, p.n_layers, p.tile_layer[e0 >> kTileShift], e0);
-        const bool whole = (e0 + kWaveTile <= p.n) && (p.off[l0 + 1] >= e0 + kWaveTile);
-        uint32_t b[4];
-
-        if (whole) {
-            // ---- fast path: the tile lies inside layer l0 ----
-            const float4* gp = reinterpret_cast<const float4*>(g + e0) + lane;
-            const float4 v0 = gp[0], v1 = gp[64], v2 = gp[128], v3 = gp[192];
-            const float tau = p.tau[(int64_t)w * p.n_layers + l0];
-            const float s17 = p.s_shared[l0] * 0x1p-17f;
-            const float s16 = s17 * 2.0f;
+        // the data loads depend on nothing but the tile index: issue them before the
+        // (dependent) table lookups so that the two latencies overlap
+        const bool inside = e0 + kWaveTile <= p.n;
+        float4 v[4];
+        uint32_t ra[2][2], rb[2][2];   // random words of quarters 2P (ra) and 2P+1 (rb)
+        if (inside) {
+            const float* gp = g + e0 + 4 * lane;
+#pragma unroll
+            for (int k = 0; k < 4; ++k) v[k] = load_stream(gp + 256 * k);
             // Philox blocks of this tile: q0 .. q0+127; lane computes q0 + 64P + 32*par + (lane>>1)
             const uint64_t q = (uint64_t)(e0 >> 3) + (uint32_t)(32 * par + (lane >> 1));
 #pragma unroll
@@ -91,12 +90,23 @@ __global__ void __launch_bounds__(kBlock) ternarize_pack_kernel(const TernArgs p
                 // the odd lane's block; the even lane takes its words 0,1, the odd lane keeps 2,3.
                 const uint32_t nx = swap_adjacent(R.x), ny = swap_adjacent(R.y);
                 const uint32_t nz = swap_adjacent(R.z), nw = swap_adjacent(R.w);
-                const uint32_t a0 = par ? nz : R.x, a1 = par ? nw : R.y;
-                const uint32_t b0 = par ? R.z : nx, b1 = par ? R.w : ny;
-                const float4 va = P ? v2 : v0;   // quarter 2P
-                const float4 vb = P ? v3 : v1;   // quarter 2P+1
-                b[2 * P] = encode4(va, a0, a1, tau, s16, s17);
-                b[2 * P + 1] = encode4(vb, b0, b1, tau, s16, s17);
+                ra[P][0] = par ? nz : R.x, ra[P][1] = par ? nw : R.y;
+                rb[P][0] = par ? R.z : nx, rb[P][1] = par ? R.w : ny;
+            }
+        }
+        const int l0 = layer_from(p.off, p.n_layers, p.tile_layer[e0 >> kTileShift], e0);
+        const bool whole = inside && (p.off[l0 + 1] >= e0 + kWaveTile);
+        uint32_t b[4];
+
+        if (whole) {
+            // ---- fast path: the tile lies inside layer l0 ----
+            const float tau = p.tau[(int64_t)w * p.n_layers + l0];
+            const float s17 = p.s_shared[l0] * 0x1p-17f;
+            const float s16 = s17 * 2.0f;
+#pragma unroll
+            for (int P = 0; P < 2; ++P) {
+                b[2 * P] = encode4(v[2 * P], ra[P][0], ra[P][1], tau, s16, s17);
+                b[2 * P + 1] = encode4(v[2 * P + 1], rb[P][0], rb[P][1], tau, s16, s17);
             }
         } else {
             // ---- boundary path: layer changes inside the tile, or the tile is ragged ----
@@ -139,8 +149,6 @@ __global__ void __launch_bounds__(kBlock) ternarize_pack_kernel(const TernArgs p
         const uint32_t dw = lds[wave][lane];
         const int64_t byte0 = (e0 >> 2) + 4 * lane;
         if (byte0 < p.packed_bytes) *reinterpret_cast<uint32_t*>(codes + byte0) = dw;
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-        __builtin_amdgcn_wave_barrier();   // the row is rewritten by the next step
     }
 }
 

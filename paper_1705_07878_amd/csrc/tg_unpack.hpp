@@ -29,7 +29,6 @@ struct UnpackArgs {
     int64_t packed_bytes;
     int32_t n_layers;
     int32_t n_workers;
-    int32_t tiles_per_wave;
 };
 
 struct Nib {
@@ -97,12 +96,12 @@ __global__ void __launch_bounds__(kBlock) unpack_average_kernel(const UnpackArgs
     const int wave = wave_uniform(threadIdx.x >> 6);
     const int W = p.n_workers;
     const float fW = (float)W;
-    const int64_t first = ((int64_t)blockIdx.x * (kBlock / kWave) + wave) * p.tiles_per_wave;
     const uint32_t bias = (uint32_t)(128 - 2 * W) * 0x01010101u;
 
-    for (int it = 0; it < p.tiles_per_wave; ++it) {
-        const int64_t wt = first + it;
-        if (wt >= p.n_wave_tiles) break;
+    {
+        // one tile per wave (see ternarize_pack_kernel)
+        const int64_t wt = (int64_t)blockIdx.x * (kBlock / kWave) + wave;
+        if (wt >= p.n_wave_tiles) return;
         const int64_t e0 = wt * kWaveTile;
         const int64_t byte0 = (e0 >> 2) + 4 * lane;
         const bool in_codes = byte0 < p.packed_bytes;      // false only in the ragged last tile
@@ -155,8 +154,6 @@ __global__ void __launch_bounds__(kBlock) unpack_average_kernel(const UnpackArgs
                 }
             }
         }
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-        __builtin_amdgcn_wave_barrier();   // the row is rewritten by the next step
     }
 }
 

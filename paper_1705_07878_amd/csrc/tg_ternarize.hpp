@@ -53,6 +53,24 @@ __device__ __forceinline__ uint32_t encode4(const float4 v, const uint32_t wa, c
     return acc;   // code of g[i] at bits 2i..2i+1: 00 / 01 / 11
 }
 
+// The same for 4 elements that may lie in different layers: per-element tau and s17.
+__device__ __forceinline__ uint32_t encode4v(const float4 v, const uint32_t wa, const uint32_t wb,
+                                             const float tau[4], const float s17[4]) {
+    const float g[4] = {v.x, v.y, v.z, v.w};
+    const uint32_t r[4] = {wa & 0xFFFFu, wa >> 16, wb & 0xFFFFu, wb >> 16};
+    uint32_t acc = 0;
+#pragma unroll
+    for (int i = 3; i >= 0; --i) {
+        const float thr = __builtin_fmaf((float)r[i], s17[i] * 2.0f, s17[i]);
+        const uint32_t gb = __float_as_uint(g[i]);
+        const uint32_t ab = __float_as_uint(min_abs(g[i], tau[i]));
+        const uint32_t d = __float_as_uint(thr) - ab;
+        acc = __builtin_amdgcn_alignbit(acc, d & gb, 31);
+        acc = __builtin_amdgcn_alignbit(acc, d, 31);
+    }
+    return acc;
+}
+
 __global__ void __launch_bounds__(kBlock) ternarize_pack_kernel(const TernArgs p) {
     __shared__ uint32_t lds[kBlock / kWave][kWave];   // 256 B per wave
 
@@ -64,92 +82,101 @@ __global__ void __launch_bounds__(kBlock) ternarize_pack_kernel(const TernArgs p
     const uint32_t worker = p.worker_base + (uint32_t)w;
     const int par = lane & 1;
 
-    {
-        // one tile per wave: short-lived waves and a very large grid stream best here, and
-        // without a loop every table lookup below is a scalar load
-        const int64_t wt = (int64_t)blockIdx.x * (kBlock / kWave) + wave;
-        if (wt >= p.n_wave_tiles) return;
-        const int64_t e0 = wt * kWaveTile;
-        // the data loads depend on nothing but the tile index: issue them before the
-        // (dependent) table lookups so that the two latencies overlap
-        const bool inside = e0 + kWaveTile <= p.n;
-        float4 v[4];
-        uint32_t ra[2][2], rb[2][2];   // random words of quarters 2P (ra) and 2P+1 (rb)
-        if (inside) {
-            const float* gp = g + e0 + 4 * lane;
-#pragma unroll
-            for (int k = 0; k < 4; ++k) v[k] = load_stream(gp + 256 * k);
-            // Philox blocks of this tile: q0 .. q0+127; lane computes q0 + 64P + 32*par + (lane>>1)
-            const uint64_t q = (uint64_t)(e0 >> 3) + (uint32_t)(32 * par + (lane >> 1));
-#pragma unroll
-            for (int P = 0; P < 2; ++P) {
-                const uint64_t qq = q + 64 * P;
-                const U4 R = philox4x32_10((uint32_t)qq, (uint32_t)(qq >> 32), worker, p.step, p.key0, p.key1);
-                // quarter 2P: elements 8j..8j+7 belong to the even lane's block; the even lane
-                // uses its words 0,1, the odd lane the even lane's words 2,3.  Quarter 2P+1:
-                // the odd lane's block; the even lane takes its words 0,1, the odd lane keeps 2,3.
-                const uint32_t nx = swap_adjacent(R.x), ny = swap_adjacent(R.y);
-                const uint32_t nz = swap_adjacent(R.z), nw = swap_adjacent(R.w);
-                ra[P][0] = par ? nz : R.x, ra[P][1] = par ? nw : R.y;
-                rb[P][0] = par ? R.z : nx, rb[P][1] = par ? R.w : ny;
-            }
-        }
-        const int l0 = layer_from(p.off, p.n_layers, p.tile_layer[e0 >> kTileShift], e0);
-        const bool whole = inside && (p.off[l0 + 1] >= e0 + kWaveTile);
-        uint32_t b[4];
+    // one tile per wave: short-lived waves and a very large grid stream best here, and
+    // without a loop every table lookup below is a scalar load
+    const int64_t wt = (int64_t)blockIdx.x * (kBlock / kWave) + wave;
+    if (wt >= p.n_wave_tiles) return;
+    const int64_t e0 = wt * kWaveTile;
 
-        if (whole) {
-            // ---- fast path: the tile lies inside layer l0 ----
-            const float tau = p.tau[(int64_t)w * p.n_layers + l0];
-            const float s17 = p.s_shared[l0] * 0x1p-17f;
-            const float s16 = s17 * 2.0f;
+    // the data loads depend on nothing but the tile index: issue them before the
+    // (dependent) table lookups so that the two latencies overlap
+    const bool inside = e0 + kWaveTile <= p.n;
+    float4 v[4];
+    if (inside) {
+        const float* gp = g + e0 + 4 * lane;
 #pragma unroll
-            for (int P = 0; P < 2; ++P) {
-                b[2 * P] = encode4(v[2 * P], ra[P][0], ra[P][1], tau, s16, s17);
-                b[2 * P + 1] = encode4(v[2 * P + 1], rb[P][0], rb[P][1], tau, s16, s17);
-            }
-        } else {
-            // ---- boundary path: layer changes inside the tile, or the tile is ragged ----
-#pragma unroll 1
-            for (int k = 0; k < 4; ++k) {
-                const int64_t e = e0 + 256 * k + 4 * lane;
-                uint32_t byte = 0;
-                if (e < p.n) {
-                    const uint64_t qq = (uint64_t)(e >> 3);
-                    const U4 R = philox4x32_10((uint32_t)qq, (uint32_t)(qq >> 32), worker, p.step, p.key0, p.key1);
-                    const uint32_t wa = (e & 4) ? R.z : R.x, wb = (e & 4) ? R.w : R.y;
-                    int l = l0;
-#pragma unroll 1
-                    for (int i = 0; i < 4; ++i) {
-                        if (e + i >= p.n) break;
-                        l = layer_from(p.off, p.n_layers, l, e + i);
-                        const float tau = p.tau[(int64_t)w * p.n_layers + l];
-                        const float s17 = p.s_shared[l] * 0x1p-17f;
-                        const float s16 = s17 * 2.0f;
-                        const uint32_t word = (i & 2) ? wb : wa;
-                        const uint32_t r = (i & 1) ? (word >> 16) : (word & 0xFFFFu);
-                        const float thr = __builtin_fmaf((float)r, s16, s17);
-                        const uint32_t gb = __float_as_uint(g[e + i]);
-                        const uint32_t ab = __float_as_uint(min_abs(g[e + i], tau));
-                        const uint32_t d = __float_as_uint(thr) - ab;
-                        byte |= ((d >> 31) | (((d & gb) >> 31) << 1)) << (2 * i);
-                    }
-                }
-                b[k] = byte;
-            }
+        for (int k = 0; k < 4; ++k) v[k] = load_stream(gp + 256 * k);
+    } else {
+        // ragged end of the buffer: elements past n read as 0, which encodes to 00
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const int64_t e = e0 + 256 * k + 4 * lane;
+            float t[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) t[i] = (e + i < p.n) ? g[e + i] : 0.0f;
+            v[k] = make_float4(t[0], t[1], t[2], t[3]);
         }
-
-        // ---- transpose bytes (position 64k + lane) into dwords (position 4*lane) ----
-        uint8_t* row = reinterpret_cast<uint8_t*>(lds[wave]);
-#pragma unroll
-        for (int k = 0; k < 4; ++k) row[64 * k + lane] = (uint8_t)b[k];
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-        __builtin_amdgcn_wave_barrier();
-        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-        const uint32_t dw = lds[wave][lane];
-        const int64_t byte0 = (e0 >> 2) + 4 * lane;
-        if (byte0 < p.packed_bytes) *reinterpret_cast<uint32_t*>(codes + byte0) = dw;
     }
+
+    // Philox blocks of this tile: q0 .. q0+127; lane computes q0 + 64P + 32*par + (lane>>1)
+    uint32_t ra[2][2], rb[2][2];   // random words of quarters 2P (ra) and 2P+1 (rb)
+    const uint64_t q = (uint64_t)(e0 >> 3) + (uint32_t)(32 * par + (lane >> 1));
+#pragma unroll
+    for (int P = 0; P < 2; ++P) {
+        const uint64_t qq = q + 64 * P;
+        const U4 R = philox4x32_10((uint32_t)qq, (uint32_t)(qq >> 32), worker, p.step, p.key0, p.key1);
+        // quarter 2P: elements 8j..8j+7 belong to the even lane's block; the even lane
+        // uses its words 0,1, the odd lane the even lane's words 2,3.  Quarter 2P+1:
+        // the odd lane's block; the even lane takes its words 0,1, the odd lane keeps 2,3.
+        const uint32_t nx = swap_adjacent(R.x), ny = swap_adjacent(R.y);
+        const uint32_t nz = swap_adjacent(R.z), nw = swap_adjacent(R.w);
+        ra[P][0] = par ? nz : R.x, ra[P][1] = par ? nw : R.y;
+        rb[P][0] = par ? R.z : nx, rb[P][1] = par ? R.w : ny;
+    }
+
+    const int l0 = layer_from(p.off, p.n_layers, p.tile_layer[e0 >> kTileShift], e0);
+    const bool whole = p.off[l0 + 1] >= e0 + kWaveTile || l0 + 1 >= p.n_layers;
+    const float* __restrict__ tau_w = p.tau + (int64_t)w * p.n_layers;
+    uint32_t b[4];
+
+    if (whole) {
+        // ---- the tile lies inside layer l0 ----
+        const float tau = tau_w[l0];
+        const float s17 = p.s_shared[l0] * 0x1p-17f;
+        const float s16 = s17 * 2.0f;
+#pragma unroll
+        for (int P = 0; P < 2; ++P) {
+            b[2 * P] = encode4(v[2 * P], ra[P][0], ra[P][1], tau, s16, s17);
+            b[2 * P + 1] = encode4(v[2 * P + 1], rb[P][0], rb[P][1], tau, s16, s17);
+        }
+    } else {
+        // ---- layers change inside the tile.  The layer of an element at tile position x is
+        // l0 + #{ j > l0 : off[j] - e0 <= x }: one scalar pass over the (few) boundaries inside
+        // the tile, compared against all of the lane's positions at once; then tau and s are
+        // gathered per element.
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const int x0 = 256 * k + 4 * lane;
+            int l[4] = {l0, l0, l0, l0};
+            for (int j = l0 + 1; j < p.n_layers; ++j) {
+                const int64_t rel = p.off[j] - e0;
+                if (rel >= kWaveTile) break;
+                const int r = (int)rel;
+#pragma unroll
+                for (int i = 0; i < 4; ++i) l[i] += (x0 + i >= r) ? 1 : 0;
+            }
+            float tau[4], s17[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                tau[i] = tau_w[l[i]];
+                s17[i] = p.s_shared[l[i]] * 0x1p-17f;
+            }
+            const int P = k >> 1;
+            b[k] = (k & 1) ? encode4v(v[k], rb[P][0], rb[P][1], tau, s17)
+                           : encode4v(v[k], ra[P][0], ra[P][1], tau, s17);
+        }
+    }
+
+    // ---- transpose bytes (position 64k + lane) into dwords (position 4*lane) ----
+    uint8_t* row = reinterpret_cast<uint8_t*>(lds[wave]);
+#pragma unroll
+    for (int k = 0; k < 4; ++k) row[64 * k + lane] = (uint8_t)b[k];
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    const uint32_t dw = lds[wave][lane];
+    const int64_t byte0 = (e0 >> 2) + 4 * lane;
+    if (byte0 < p.packed_bytes) *reinterpret_cast<uint32_t*>(codes + byte0) = dw;
 }
 
 }  // namespace tg

@@ -133,24 +133,39 @@ __global__ void __launch_bounds__(kBlock) unpack_average_kernel(const UnpackArgs
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 
         const int l0 = layer_from(p.off, p.n_layers, p.tile_layer[e0 >> kTileShift], e0);
-        const bool whole = (e0 + kWaveTile <= p.n) && (p.off[l0 + 1] >= e0 + kWaveTile);
-        if (whole) {
+        const bool one_layer = p.off[l0 + 1] >= e0 + kWaveTile || l0 + 1 >= p.n_layers;
+        if (one_layer && e0 + kWaveTile <= p.n) {
             const float sc = p.s_shared[l0] / fW;
             float* dst = p.avg + e0 + 4 * lane;
 #pragma unroll
             for (int k = 0; k < 4; ++k) store4<NT>(dst + 256 * k, scale4(row[64 * k + lane], sc));
         } else {
-#pragma unroll 1
+            // layers change inside the tile, or the tile is ragged: the layer of the element at
+            // tile position x is l0 + #{ j > l0 : off[j] - e0 <= x } (one scalar pass over the
+            // boundaries inside the tile); one scale per element
+#pragma unroll
             for (int k = 0; k < 4; ++k) {
-                const int64_t e = e0 + 256 * k + 4 * lane;
-                const uint32_t d = row[64 * k + lane];
-                int l = l0;
-#pragma unroll 1
-                for (int i = 0; i < 4; ++i) {
-                    if (e + i >= p.n) break;
-                    l = layer_from(p.off, p.n_layers, l, e + i);
-                    const float sc = p.s_shared[l] / fW;
-                    p.avg[e + i] = (float)(int)(int8_t)(d >> (8 * i)) * sc;
+                const int x0 = 256 * k + 4 * lane;
+                const int64_t e = e0 + x0;
+                int l[4] = {l0, l0, l0, l0};
+                for (int j = l0 + 1; j < p.n_layers; ++j) {
+                    const int64_t rel = p.off[j] - e0;
+                    if (rel >= kWaveTile) break;
+                    const int r = (int)rel;
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) l[i] += (x0 + i >= r) ? 1 : 0;
+                }
+                const int d = (int)row[64 * k + lane];
+                const int kk[4] = {(int)(int8_t)d, (int)(int8_t)(d >> 8), (int)(int8_t)(d >> 16), d >> 24};
+                float o[4];
+#pragma unroll
+                for (int i = 0; i < 4; ++i) o[i] = (float)kk[i] * (p.s_shared[l[i]] / fW);
+                if (e + 3 < p.n) {
+                    store4<NT>(p.avg + e, make_float4(o[0], o[1], o[2], o[3]));
+                } else {
+#pragma unroll
+                    for (int i = 0; i < 4; ++i)
+                        if (e + i < p.n) p.avg[e + i] = o[i];
                 }
             }
         }

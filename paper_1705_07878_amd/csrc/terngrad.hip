@@ -29,11 +29,10 @@ bool hip_ok(hipError_t e) {
 }
 
 struct Tables {
-    int64_t n = 0, n_tiles = 0, n_chunks = 0;
+    int64_t n = 0, n_tiles = 0, chunk = 0;
     std::vector<int32_t> tile_layer;
-    std::vector<int64_t> chunk_seg;   // [n_chunks+1]
     std::vector<int32_t> seg_layer;
-    std::vector<int64_t> seg_begin, seg_end;
+    std::vector<int64_t> seg_begin, seg_end, seg_pivot;
     std::vector<int64_t> layer_seg;   // [L+1]
 };
 
@@ -51,7 +50,8 @@ void build_tables(int64_t L, const int64_t* off, Tables& T) {
     const int64_t tile = (int64_t)1 << tg::kTileShift;
     T.n = n;
     T.n_tiles = (n + tile - 1) / tile;
-    T.n_chunks = (n + tg::kStatChunk - 1) / tg::kStatChunk;
+    T.chunk = n >= tg::kStatLargeFrom ? tg::kStatChunkLarge : tg::kStatChunk;
+    const int64_t n_chunks = (n + T.chunk - 1) / T.chunk;
     T.tile_layer.resize((size_t)T.n_tiles);
     int64_t l = 0;
     for (int64_t t = 0; t < T.n_tiles; ++t) {
@@ -59,14 +59,12 @@ void build_tables(int64_t L, const int64_t* off, Tables& T) {
         while (e >= off[l + 1]) ++l;          // e < n = off[L]: stops at the layer that holds e
         T.tile_layer[(size_t)t] = (int32_t)l;
     }
-    T.chunk_seg.assign((size_t)T.n_chunks + 1, 0);
     T.layer_seg.assign((size_t)L + 1, 0);
     l = 0;
     int64_t next_layer_mark = 0;              // layers < this already have layer_seg set
-    for (int64_t c = 0; c < T.n_chunks; ++c) {
-        T.chunk_seg[(size_t)c] = (int64_t)T.seg_layer.size();
-        const int64_t cb = c * tg::kStatChunk;
-        const int64_t ce = (cb + tg::kStatChunk < n) ? cb + tg::kStatChunk : n;
+    for (int64_t c = 0; c < n_chunks; ++c) {
+        const int64_t cb = c * T.chunk;
+        const int64_t ce = (cb + T.chunk < n) ? cb + T.chunk : n;
         int64_t pos = cb;
         while (pos < ce) {
             while (pos >= off[l + 1]) ++l;
@@ -75,10 +73,10 @@ void build_tables(int64_t L, const int64_t* off, Tables& T) {
             T.seg_layer.push_back((int32_t)l);
             T.seg_begin.push_back(pos);
             T.seg_end.push_back(end);
+            T.seg_pivot.push_back(off[l]);
             pos = end;
         }
     }
-    T.chunk_seg[(size_t)T.n_chunks] = (int64_t)T.seg_layer.size();
     while (next_layer_mark <= L) T.layer_seg[(size_t)next_layer_mark++] = (int64_t)T.seg_layer.size();
 }
 
@@ -95,14 +93,13 @@ bool aligned(const void* p, uintptr_t a) { return ((uintptr_t)p & (a - 1)) == 0;
 }  // namespace
 
 struct tg_plan {
-    int64_t n_layers = 0, n = 0, packed_bytes = 0, n_tiles = 0, n_chunks = 0, n_segs = 0;
+    int64_t n_layers = 0, n = 0, packed_bytes = 0, n_tiles = 0, n_segs = 0;
     int max_workers = 0;
     int64_t* d_off = nullptr;
     int32_t* d_tile_layer = nullptr;
-    int64_t* d_chunk_seg = nullptr;
-    int32_t* d_seg_layer = nullptr;
     int64_t* d_seg_begin = nullptr;
     int64_t* d_seg_end = nullptr;
+    int64_t* d_seg_pivot = nullptr;
     int64_t* d_layer_seg = nullptr;
     double* d_psum = nullptr;
     double* d_psq = nullptr;
@@ -137,7 +134,7 @@ tg_status tg_describe_tables(int64_t n_layers, const int64_t* offsets,
         return TG_ERR_ALLOC;
     }
     if (tile_elems) *tile_elems = (int64_t)1 << tg::kTileShift;
-    if (chunk_elems) *chunk_elems = tg::kStatChunk;
+    if (chunk_elems) *chunk_elems = T.chunk;
     if (n_tiles) *n_tiles = T.n_tiles;
     if (n_segments) *n_segments = (int64_t)T.seg_layer.size();
     if (tile_layer && tile_cap >= T.n_tiles)
@@ -171,15 +168,14 @@ tg_status tg_plan_create(int64_t n_layers, const int64_t* offsets, int max_worke
     p->n = T.n;
     p->packed_bytes = (((T.n + 3) / 4) + 15) / 16 * 16;
     p->n_tiles = T.n_tiles;
-    p->n_chunks = T.n_chunks;
     p->n_segs = (int64_t)T.seg_layer.size();
     p->max_workers = max_workers;
 
     const std::vector<int64_t> off(offsets, offsets + n_layers + 1);
     const size_t np = (size_t)p->n_segs * (size_t)max_workers;
     bool ok = upload(&p->d_off, off) && upload(&p->d_tile_layer, T.tile_layer) &&
-              upload(&p->d_chunk_seg, T.chunk_seg) && upload(&p->d_seg_layer, T.seg_layer) &&
               upload(&p->d_seg_begin, T.seg_begin) && upload(&p->d_seg_end, T.seg_end) &&
+              upload(&p->d_seg_pivot, T.seg_pivot) &&
               upload(&p->d_layer_seg, T.layer_seg) &&
               hip_ok(hipMalloc((void**)&p->d_psum, np * sizeof(double))) &&
               hip_ok(hipMalloc((void**)&p->d_psq, np * sizeof(double))) &&
@@ -195,8 +191,8 @@ tg_status tg_plan_create(int64_t n_layers, const int64_t* offsets, int max_worke
 
 tg_status tg_plan_destroy(tg_plan* p) {
     if (p == nullptr) return TG_OK;
-    void* bufs[] = {p->d_off, p->d_tile_layer, p->d_chunk_seg, p->d_seg_layer, p->d_seg_begin,
-                    p->d_seg_end, p->d_layer_seg, p->d_psum, p->d_psq, p->d_pmax};
+    void* bufs[] = {p->d_off, p->d_tile_layer, p->d_seg_begin, p->d_seg_end, p->d_seg_pivot,
+                    p->d_layer_seg, p->d_psum, p->d_psq, p->d_pmax};
     bool ok = true;
     for (void* b : bufs)
         if (b != nullptr) ok = hip_ok(hipFree(b)) && ok;
@@ -226,17 +222,15 @@ tg_status tg_clip_stats(tg_plan* p, int n_workers, const float* const* grads, fl
         a.grads[w] = grads[w];
     }
     if (!aligned(tau, 4) || !aligned(s_local, 4)) return TG_ERR_ALIGNMENT;
-    a.off = p->d_off;
-    a.chunk_seg = p->d_chunk_seg;
-    a.seg_layer = p->d_seg_layer;
     a.seg_begin = p->d_seg_begin;
     a.seg_end = p->d_seg_end;
+    a.seg_pivot = p->d_seg_pivot;
     a.psum = p->d_psum;
     a.psq = p->d_psq;
     a.pmax = p->d_pmax;
     a.n_segs = p->n_segs;
     hipStream_t s = (hipStream_t)stream;
-    hipLaunchKernelGGL(tg::clip_stats_partial_kernel, dim3((unsigned)p->n_chunks, (unsigned)n_workers),
+    hipLaunchKernelGGL(tg::clip_stats_partial_kernel, dim3((unsigned)p->n_segs, (unsigned)n_workers),
                        dim3(tg::kBlock), 0, s, a);
     if (!hip_ok(hipGetLastError())) return TG_ERR_HIP;
 
@@ -253,7 +247,7 @@ tg_status tg_clip_stats(tg_plan* p, int n_workers, const float* const* grads, fl
     f.c = c;
     f.noclip = (!(c > 0.0f) || std::isinf(c)) ? 1 : 0;
     hipLaunchKernelGGL(tg::clip_stats_final_kernel, dim3((unsigned)p->n_layers, (unsigned)n_workers),
-                       dim3(tg::kBlock), 0, s, f);
+                       dim3(tg::kFinalBlock), 0, s, f);
     if (!hip_ok(hipGetLastError())) return TG_ERR_HIP;
     return TG_OK;
 }

@@ -3,10 +3,10 @@
 // max|clip(g)| = min(max|g|, c*sigma), so sigma and the scaler come out of the
 // same pass.  Sums are fp64 and taken about a per-layer pivot K = first element
 // of the layer (shifted-data variance: exact for a constant layer, insensitive to
-// a large mean).  No float atomics: every statistics chunk of 16384 elements is
-// cut into segments (one per layer it touches); a workgroup reduces each of its
-// segments in a fixed tree and writes one partial; a second small kernel folds
-// the partials of each layer in a fixed order.  Results are bit-identical from
+// a large mean).  No float atomics: every statistics chunk (16384 elements, 65536 for
+// gradients beyond 2^27 elements) is cut into segments, one per layer it touches; one
+// workgroup reduces one segment in a fixed tree and writes one partial; a second small
+// kernel folds the partials of each layer in a fixed order.  Results are bit-identical from
 // run to run.
 #pragma once
 
@@ -14,15 +14,15 @@
 
 namespace tg {
 
-constexpr int kStatChunk = 16384;   // elements per workgroup: 256 threads x 16 float4
+constexpr int kStatChunk = 16384;       // elements per workgroup: 256 threads x 16 float4
+constexpr int kStatChunkLarge = 65536;  // for very large gradients (fewer partials to fold)
+constexpr int64_t kStatLargeFrom = (int64_t)1 << 27;
 
 struct StatsArgs {
     const float* grads[kMaxWorkers];
-    const int64_t* off;             // [L+1]
-    const int64_t* chunk_seg;       // [n_chunks+1] first segment of each chunk
-    const int32_t* seg_layer;       // [n_segs]
     const int64_t* seg_begin;       // [n_segs]
     const int64_t* seg_end;         // [n_segs]
+    const int64_t* seg_pivot;       // [n_segs] index of the first element of the segment's layer
     double* psum;                   // [W][n_segs] sum (g - K)
     double* psq;                    // [W][n_segs] sum (g - K)^2
     float* pmax;                    // [W][n_segs] max |g|
@@ -59,6 +59,7 @@ __device__ __forceinline__ Acc wave_reduce(Acc a) {
     return a;
 }
 
+// one workgroup per segment (a run of at most one chunk inside one layer)
 __global__ void __launch_bounds__(kBlock) clip_stats_partial_kernel(const StatsArgs p) {
     __shared__ double sh1[kBlock / kWave], sh2[kBlock / kWave];
     __shared__ float shm[kBlock / kWave];
@@ -66,61 +67,52 @@ __global__ void __launch_bounds__(kBlock) clip_stats_partial_kernel(const StatsA
     const int w = blockIdx.y;
     const float* __restrict__ g = p.grads[w];
     const int t = threadIdx.x;
-    const int64_t chunk = blockIdx.x;
-    const int64_t sb = p.chunk_seg[chunk], se = p.chunk_seg[chunk + 1];
-
-    for (int64_t sg = sb; sg < se; ++sg) {
-        const int64_t b = p.seg_begin[sg], e = p.seg_end[sg];
-        const double K = (double)g[p.off[p.seg_layer[sg]]];
-        Acc a = {0.0, 0.0, 0.0f};
-        const int64_t b4 = (b + 3) & ~(int64_t)3;
-        const int64_t e4 = e & ~(int64_t)3;
-        if (b4 < e4) {
-            const int64_t nv = (e4 - b4) >> 2;
-            if (nv == kStatChunk / 4) {
-                // whole chunk: 16 loads per thread, four in flight at a time
+    const int64_t sg = blockIdx.x;
+    const int64_t b = p.seg_begin[sg], e = p.seg_end[sg];
+    const double K = (double)g[p.seg_pivot[sg]];
+    Acc a = {0.0, 0.0, 0.0f};
+    const int64_t b4 = (b + 3) & ~(int64_t)3;
+    const int64_t e4 = e & ~(int64_t)3;
+    if (b4 < e4) {
+        const float* gp = g + b4;
+        const int64_t nv = (e4 - b4) >> 2;          // float4 groups
+        int64_t i = t;
+        // four streaming loads in flight per thread
+        for (; i + 3 * kBlock < nv; i += 4 * kBlock) {
+            const float4 v0 = load_stream(gp + 4 * i), v1 = load_stream(gp + 4 * (i + kBlock));
+            const float4 v2 = load_stream(gp + 4 * (i + 2 * kBlock)), v3 = load_stream(gp + 4 * (i + 3 * kBlock));
+            acc_add4(a, v0, K);
+            acc_add4(a, v1, K);
+            acc_add4(a, v2, K);
+            acc_add4(a, v3, K);
+        }
+        for (; i < nv; i += kBlock) acc_add4(a, load_stream(gp + 4 * i), K);
+        // ragged head and tail, at most 3 elements each
+        if (t < b4 - b) acc_add(a, g[b + t], K);
+        if (t < e - e4) acc_add(a, g[e4 + t], K);
+    } else {
+        for (int64_t i = b + t; i < e; i += kBlock) acc_add(a, g[i], K);
+    }
+    a = wave_reduce(a);
+    if ((t & 63) == 0) {
+        sh1[t >> 6] = a.s1;
+        sh2[t >> 6] = a.s2;
+        shm[t >> 6] = a.m;
+    }
+    __syncthreads();
+    if (t == 0) {
+        double s1 = sh1[0], s2 = sh2[0];
+        float m = shm[0];
 #pragma unroll
-                for (int j = 0; j < 16; j += 4) {
-                    const float* q = g + b4 + 4 * ((int64_t)j * kBlock + t);
-                    const float4 v0 = load_stream(q), v1 = load_stream(q + 4 * kBlock);
-                    const float4 v2 = load_stream(q + 8 * kBlock), v3 = load_stream(q + 12 * kBlock);
-                    acc_add4(a, v0, K);
-                    acc_add4(a, v1, K);
-                    acc_add4(a, v2, K);
-                    acc_add4(a, v3, K);
-                }
-            } else {
-                for (int64_t i = t; i < nv; i += kBlock) acc_add4(a, load_stream(g + b4 + 4 * i), K);
-            }
-            // ragged head and tail, at most 3 elements each
-            if (t < b4 - b) acc_add(a, g[b + t], K);
-            if (t < e - e4) acc_add(a, g[e4 + t], K);
-        } else {
-            for (int64_t i = b + t; i < e; i += kBlock) acc_add(a, g[i], K);
+        for (int k = 1; k < kBlock / kWave; ++k) {
+            s1 += sh1[k];
+            s2 += sh2[k];
+            m = fmaxf(m, shm[k]);
         }
-        a = wave_reduce(a);
-        const int wave = t >> 6;
-        if ((t & 63) == 0) {
-            sh1[wave] = a.s1;
-            sh2[wave] = a.s2;
-            shm[wave] = a.m;
-        }
-        __syncthreads();
-        if (t == 0) {
-            double s1 = sh1[0], s2 = sh2[0];
-            float m = shm[0];
-#pragma unroll
-            for (int k = 1; k < kBlock / kWave; ++k) {
-                s1 += sh1[k];
-                s2 += sh2[k];
-                m = fmaxf(m, shm[k]);
-            }
-            const int64_t o = (int64_t)w * p.n_segs + sg;
-            p.psum[o] = s1;
-            p.psq[o] = s2;
-            p.pmax[o] = m;
-        }
-        __syncthreads();
+        const int64_t o = (int64_t)w * p.n_segs + sg;
+        p.psum[o] = s1;
+        p.psq[o] = s2;
+        p.pmax[o] = m;
     }
 }
 
@@ -138,15 +130,17 @@ struct StatsFinalArgs {
     int32_t noclip;
 };
 
-__global__ void __launch_bounds__(kBlock) clip_stats_final_kernel(const StatsFinalArgs p) {
-    __shared__ double sh1[kBlock / kWave], sh2[kBlock / kWave];
-    __shared__ float shm[kBlock / kWave];
+constexpr int kFinalBlock = 1024;
+
+__global__ void __launch_bounds__(kFinalBlock) clip_stats_final_kernel(const StatsFinalArgs p) {
+    __shared__ double sh1[kFinalBlock / kWave], sh2[kFinalBlock / kWave];
+    __shared__ float shm[kFinalBlock / kWave];
 
     const int l = blockIdx.x, w = blockIdx.y, t = threadIdx.x;
     const int64_t sb = p.layer_seg[l], se = p.layer_seg[l + 1];
     const int64_t base = (int64_t)w * p.n_segs;
     Acc a = {0.0, 0.0, 0.0f};
-    for (int64_t i = sb + t; i < se; i += kBlock) {
+    for (int64_t i = sb + t; i < se; i += kFinalBlock) {
         a.s1 += p.psum[base + i];
         a.s2 += p.psq[base + i];
         a.m = fmaxf(a.m, p.pmax[base + i]);
@@ -162,7 +156,7 @@ __global__ void __launch_bounds__(kBlock) clip_stats_final_kernel(const StatsFin
         double s1 = sh1[0], s2 = sh2[0];
         float m = shm[0];
 #pragma unroll
-        for (int k = 1; k < kBlock / kWave; ++k) {
+        for (int k = 1; k < kFinalBlock / kWave; ++k) {
             s1 += sh1[k];
             s2 += sh2[k];
             m = fmaxf(m, shm[k]);

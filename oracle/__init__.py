@@ -60,6 +60,9 @@ def lib() -> ctypes.CDLL:
         L.tgo_code_at.restype = ctypes.c_int
         L.tgo_unpack_average.argtypes = [ctypes.POINTER(c_u8), ctypes.c_int, ctypes.c_int64, c_i64, c_f, c_f]
         L.tgo_unpack_average.restype = None
+        L.tgo_unpack_update.argtypes = [ctypes.POINTER(c_u8), ctypes.c_int, ctypes.c_int64, c_i64, c_f,
+                                        ctypes.c_float, c_f]
+        L.tgo_unpack_update.restype = None
         _lib = L
     return _lib
 
@@ -160,3 +163,23 @@ def unpack_average(codes_list, off, s_shared):
     avg = np.empty(n, np.float32)
     lib().tgo_unpack_average(arr, W, L, op, sp, _f32(avg)[1])
     return avg
+
+
+def unpack_update(codes_list, off, s_shared, eta, weights):
+    """-> new float32 weights [n] = w - eta * average of the decoded codes (input not modified)."""
+    off = _check_offsets(off)
+    _, op = _i64(off)
+    L = off.size - 1
+    n = int(off[-1])
+    keep = [np.ascontiguousarray(c, dtype=np.uint8) for c in codes_list]
+    for c in keep:
+        assert c.size >= (n + 3) // 4
+    W = len(keep)
+    u8p = ctypes.POINTER(ctypes.c_uint8)
+    arr = (u8p * W)(*[c.ctypes.data_as(u8p) for c in keep])
+    s_shared, sp = _f32(s_shared)
+    assert s_shared.size == L
+    w = np.array(weights, dtype=np.float32, copy=True)
+    assert w.size == n
+    lib().tgo_unpack_update(arr, W, L, op, sp, np.float32(eta), _f32(w)[1])
+    return w

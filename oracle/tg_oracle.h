@@ -88,6 +88,13 @@ int tgo_code_at(const uint8_t* codes, int64_t e);
 void tgo_unpack_average(const uint8_t* const* codes, int n_workers, int64_t n_layers,
                         const int64_t* off, const float* s_shared, float* avg);
 
+/* Algorithm 1, worker line "update parameters", applied directly to the pulled codes:
+ *   w_e <- (float)( (double)w_e - (double)eta * k_e * s_shared_l / W ),
+ * i.e. w - eta * avg with avg as in tgo_unpack_average but never rounded to fp32.
+ * weights: [n], updated in place. */
+void tgo_unpack_update(const uint8_t* const* codes, int n_workers, int64_t n_layers,
+                       const int64_t* off, const float* s_shared, float eta, float* weights);
+
 #ifdef __cplusplus
 }
 #endif

@@ -372,3 +372,46 @@ def test_zero_fraction_on_gaussian_matches_expectation(oracle):
     want_zero = 1 - e_min / c
     assert abs((1 - nz / n) - want_zero) < 5e-3
     assert abs(100 * want_zero - PAPER["alexnet_fc6_zero_fraction_percent"]["value"]) < 5
+
+
+# --------------------------------------------------------------------------
+# Algorithm 1, "update parameters": w <- w - eta * average
+# --------------------------------------------------------------------------
+def test_unpack_update_is_w_minus_eta_times_mean(oracle):
+    rng = np.random.default_rng(15)
+    sizes = [9, 130, 1, 64]
+    off = np.concatenate([[0], np.cumsum(sizes)])
+    n = int(off[-1])
+    lay = np.repeat(np.arange(len(sizes)), sizes)
+    for W in (1, 3, 8):
+        s = (np.abs(rng.normal(size=len(sizes))) + 0.1).astype(np.float32)
+        ts = [rng.integers(-1, 2, size=n) for _ in range(W)]
+        codes = [_forced(oracle, t) for t in ts]
+        w0 = rng.normal(size=n).astype(np.float32)
+        eta = np.float32(0.05)
+        w1 = oracle.unpack_update(codes, off, s, eta, w0)
+        mean = np.mean([t * s[lay].astype(np.float64) for t in ts], axis=0)        # textbook mean
+        want = w0.astype(np.float64) - float(eta) * mean
+        assert np.allclose(w1, want, rtol=2e-7, atol=0)
+        k = np.sum(ts, axis=0)
+        assert np.array_equal(w1[k == 0], w0[k == 0])                               # untouched where avg = 0
+        assert np.array_equal(oracle.unpack_update(codes, off, s, 0.0, w0), w0)    # eta = 0
+
+
+def test_terngrad_sgd_converges_on_a_convex_problem(oracle):
+    """Theorem 1 on C(w) = |w - w*|^2 / 2: noisy gradients, ternarized per worker with clipping and a
+    shared scaler, averaged, learning rate with sum = inf and sum of squares < inf."""
+    rng = np.random.default_rng(16)
+    sizes = [40, 24]
+    off = np.concatenate([[0], np.cumsum(sizes)])
+    n, W = int(off[-1]), 4
+    w_star = rng.normal(size=n).astype(np.float32)
+    w = np.zeros(n, np.float32)
+    d0 = float(np.linalg.norm(w - w_star))
+    for t in range(1500):
+        grads = [(w - w_star + 0.3 * rng.normal(size=n)).astype(np.float32) for _ in range(W)]
+        st = [oracle.clip_stats(g, off, 2.5) for g in grads]
+        s = oracle.share_scalers(np.stack([x[1] for x in st]))
+        codes = [oracle.ternarize_pack(g, off, st[i][0], s, seed=7, step=t, worker=i) for i, g in enumerate(grads)]
+        w = oracle.unpack_update(codes, off, s, 0.5 / (1.0 + t / 50.0), w)
+    assert float(np.linalg.norm(w - w_star)) < 0.05 * d0

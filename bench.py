@@ -134,6 +134,23 @@ def main():
     kern["ternarize_pack"]["fp32_in_GBps"] = round(in_bytes / (call_ms["ternarize_pack"] * 1e-3) / 1e9, 1)
     kern["share_scalers"] = {"ms": round(call_ms["share_scalers"], 4)}
 
+    # next line of Algorithm 1 (not part of the timed step): decode fused with the parameter update
+    weights = torch.zeros((n,), dtype=torch.float32, device="cuda")
+    for _ in range(3):
+        plan.tg_unpack_update(codes, s_shared, 1e-3, weights)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    reps = max(5, args.steps // 2)
+    e0.record(stream)
+    for _ in range(reps):
+        plan.tg_unpack_update(codes, s_shared, 1e-3, weights)
+    e1.record(stream)
+    torch.cuda.synchronize()
+    upd_ms = e0.elapsed_time(e1) / reps
+    upd_gbs = n * (8.0 + 0.25 * W) / (upd_ms * 1e-3) / 1e9
+    kern["unpack_update (not in step)"] = {"ms": round(upd_ms, 4), "algorithmic_GBps": round(upd_gbs, 1),
+                                           "pct_hbm_peak": round(100 * upd_gbs / HBM_PEAK_GBS, 1)}
+    del weights
+
     dom = "ternarize_pack"
     achieved = alg_bytes[dom] / (call_ms[dom] * 1e-3) / 1e9
     roofline = {"bound": "hbm", "kernel": "tg::ternarize_pack_kernel", "achieved": round(achieved, 1),

@@ -143,6 +143,19 @@ tg_status tg_ternarize_pack(tg_plan* plan, int n_workers, uint32_t worker_base,
 tg_status tg_unpack_average(tg_plan* plan, int n_workers, const uint8_t* const* codes,
                             const float* s_shared, float* avg, void* stream);
 
+/* ---- beyond the four calls: the next line of Algorithm 1 ------------------- */
+
+/* Algorithm 1, worker lines "pull averaged gradients" + "update parameters" in one pass:
+ *   weights[e] <- weights[e] - eta * (sum_w t_w[e]) * (s_shared[layer(e)] / n_workers)
+ * with the average formed exactly as in tg_unpack_average and applied with one fused
+ * multiply-add; it is never written to memory.  Under parameter localization (Section 3)
+ * every worker runs this on its own copy of the parameters.
+ *   codes, s_shared  as for tg_unpack_average
+ *   eta              learning rate (finite)
+ *   weights          dev [n] fp32, in/out, 16-byte aligned */
+tg_status tg_unpack_update(tg_plan* plan, int n_workers, const uint8_t* const* codes,
+                           const float* s_shared, float eta, float* weights, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -59,6 +59,8 @@ lib.tg_ternarize_pack.argtypes = [_vp, ctypes.c_int, ctypes.c_uint32, _pp, _vp, 
 lib.tg_ternarize_pack.restype = ctypes.c_int
 lib.tg_unpack_average.argtypes = [_vp, ctypes.c_int, _pp, _vp, _vp, _vp]
 lib.tg_unpack_average.restype = ctypes.c_int
+lib.tg_unpack_update.argtypes = [_vp, ctypes.c_int, _pp, _vp, ctypes.c_float, _vp, _vp]
+lib.tg_unpack_update.restype = ctypes.c_int
 
 
 class TgError(RuntimeError):
@@ -183,3 +185,8 @@ class Plan:
         cp, _k = _ptr_array(codes)
         _check(lib.tg_unpack_average(self._h, len(codes), cp, _ptr(s_shared), _ptr(avg),
                                      _stream(stream)), "tg_unpack_average")
+
+    def tg_unpack_update(self, codes: Sequence, s_shared, eta: float, weights, stream=None):
+        cp, _k = _ptr_array(codes)
+        _check(lib.tg_unpack_update(self._h, len(codes), cp, _ptr(s_shared), float(eta), _ptr(weights),
+                                    _stream(stream)), "tg_unpack_update")

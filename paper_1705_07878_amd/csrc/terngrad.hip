@@ -297,32 +297,48 @@ tg_status tg_ternarize_pack(tg_plan* p, int n_workers, uint32_t worker_base,
     return TG_OK;
 }
 
-tg_status tg_unpack_average(tg_plan* p, int n_workers, const uint8_t* const* codes,
-                            const float* s_shared, float* avg, void* stream) {
+static tg_status launch_unpack(tg_plan* p, int n_workers, const uint8_t* const* codes,
+                               const float* s_shared, float* out, bool update, float eta, void* stream) {
     tg_status st = check_workers(p, n_workers);
     if (st != TG_OK) return st;
-    if (codes == nullptr || s_shared == nullptr || avg == nullptr) return TG_ERR_INVALID_ARG;
+    if (codes == nullptr || s_shared == nullptr || out == nullptr) return TG_ERR_INVALID_ARG;
     tg::UnpackArgs a{};
     for (int w = 0; w < n_workers; ++w) {
         if (codes[w] == nullptr) return TG_ERR_INVALID_ARG;
         if (!aligned(codes[w], 4)) return TG_ERR_ALIGNMENT;
         a.codes[w] = codes[w];
     }
-    if (!aligned(s_shared, 4) || !aligned(avg, 16)) return TG_ERR_ALIGNMENT;
+    if (!aligned(s_shared, 4) || !aligned(out, 16)) return TG_ERR_ALIGNMENT;
     a.s_shared = s_shared;
     a.off = p->d_off;
     a.tile_layer = p->d_tile_layer;
-    a.avg = avg;
+    a.avg = out;
+    a.eta = eta;
     a.n = p->n;
     a.n_wave_tiles = (p->n + tg::kWaveTile - 1) / tg::kWaveTile;
     a.packed_bytes = p->packed_bytes;
     a.n_layers = (int32_t)p->n_layers;
     a.n_workers = n_workers;
     const int64_t blocks = (a.n_wave_tiles + tg::kBlock / tg::kWave - 1) / (tg::kBlock / tg::kWave);
-    hipLaunchKernelGGL(tg::unpack_average_kernel<true>, dim3((unsigned)blocks), dim3(tg::kBlock), 0,
-                       (hipStream_t)stream, a);
+    if (update)
+        hipLaunchKernelGGL((tg::unpack_average_kernel<true, true>), dim3((unsigned)blocks), dim3(tg::kBlock), 0,
+                           (hipStream_t)stream, a);
+    else
+        hipLaunchKernelGGL((tg::unpack_average_kernel<true, false>), dim3((unsigned)blocks), dim3(tg::kBlock), 0,
+                           (hipStream_t)stream, a);
     if (!hip_ok(hipGetLastError())) return TG_ERR_HIP;
     return TG_OK;
+}
+
+tg_status tg_unpack_average(tg_plan* p, int n_workers, const uint8_t* const* codes,
+                            const float* s_shared, float* avg, void* stream) {
+    return launch_unpack(p, n_workers, codes, s_shared, avg, false, 0.0f, stream);
+}
+
+tg_status tg_unpack_update(tg_plan* p, int n_workers, const uint8_t* const* codes,
+                           const float* s_shared, float eta, float* weights, void* stream) {
+    if (std::isnan(eta) || std::isinf(eta)) return TG_ERR_INVALID_ARG;
+    return launch_unpack(p, n_workers, codes, s_shared, weights, true, eta, stream);
 }
 
 }  // extern "C"

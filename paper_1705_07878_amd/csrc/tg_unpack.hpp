@@ -23,7 +23,8 @@ struct UnpackArgs {
     const float* s_shared;      // [L]
     const int64_t* off;         // [L+1]
     const int32_t* tile_layer;
-    float* avg;                 // [n]
+    float* avg;                 // [n]: the average (out), or the weights (in/out) when updating
+    float eta;                  // learning rate of the fused update
     int64_t n;
     int64_t n_wave_tiles;       // ceil(n / 1024)
     int64_t packed_bytes;
@@ -88,7 +89,16 @@ __device__ __forceinline__ void store4(float* dst, const float4 v) {
     }
 }
 
-template <bool NT>
+// w - eta * avg, one rounding
+__device__ __forceinline__ float4 apply4(const float4 w, const float4 a, const float eta) {
+    return make_float4(__builtin_fmaf(-eta, a.x, w.x), __builtin_fmaf(-eta, a.y, w.y),
+                       __builtin_fmaf(-eta, a.z, w.z), __builtin_fmaf(-eta, a.w, w.w));
+}
+
+// UPDATE = false: avg[e] = k * (s/W)                 (Algorithm 1, server line)
+// UPDATE = true:  w[e]  = w[e] - eta * k * (s/W)     (server line fused with the update line:
+//                 the average is never written to or re-read from HBM)
+template <bool NT, bool UPDATE>
 __global__ void __launch_bounds__(kBlock) unpack_average_kernel(const UnpackArgs p) {
     __shared__ uint32_t lds[kBlock / kWave][kWaveTile / 4];   // 1 KiB per wave
 
@@ -105,6 +115,13 @@ __global__ void __launch_bounds__(kBlock) unpack_average_kernel(const UnpackArgs
         const int64_t e0 = wt * kWaveTile;
         const int64_t byte0 = (e0 >> 2) + 4 * lane;
         const bool in_codes = byte0 < p.packed_bytes;      // false only in the ragged last tile
+        const bool full = e0 + kWaveTile <= p.n;
+        float4 wv[4];
+        if (UPDATE && full) {
+            // the weights depend on nothing: issue their loads first
+#pragma unroll
+            for (int k = 0; k < 4; ++k) wv[k] = load_stream(p.avg + e0 + 4 * lane + 256 * k);
+        }
 
         Byt acc = {bias, bias, bias, bias};
         for (int w0 = 0; w0 < W; w0 += 5) {
@@ -134,11 +151,15 @@ __global__ void __launch_bounds__(kBlock) unpack_average_kernel(const UnpackArgs
 
         const int l0 = layer_from(p.off, p.n_layers, p.tile_layer[e0 >> kTileShift], e0);
         const bool one_layer = p.off[l0 + 1] >= e0 + kWaveTile || l0 + 1 >= p.n_layers;
-        if (one_layer && e0 + kWaveTile <= p.n) {
+        if (one_layer && full) {
             const float sc = p.s_shared[l0] / fW;
             float* dst = p.avg + e0 + 4 * lane;
 #pragma unroll
-            for (int k = 0; k < 4; ++k) store4<NT>(dst + 256 * k, scale4(row[64 * k + lane], sc));
+            for (int k = 0; k < 4; ++k) {
+                float4 o = scale4(row[64 * k + lane], sc);
+                if (UPDATE) o = apply4(wv[k], o, p.eta);
+                store4<NT>(dst + 256 * k, o);
+            }
         } else {
             // layers change inside the tile, or the tile is ragged: the layer of the element at
             // tile position x is l0 + #{ j > l0 : off[j] - e0 <= x } (one scalar pass over the
@@ -159,7 +180,10 @@ __global__ void __launch_bounds__(kBlock) unpack_average_kernel(const UnpackArgs
                 const int kk[4] = {(int)(int8_t)d, (int)(int8_t)(d >> 8), (int)(int8_t)(d >> 16), d >> 24};
                 float o[4];
 #pragma unroll
-                for (int i = 0; i < 4; ++i) o[i] = (float)kk[i] * (p.s_shared[l[i]] / fW);
+                for (int i = 0; i < 4; ++i) {
+                    o[i] = (float)kk[i] * (p.s_shared[l[i]] / fW);
+                    if (UPDATE && e + i < p.n) o[i] = __builtin_fmaf(-p.eta, o[i], p.avg[e + i]);
+                }
                 if (e + 3 < p.n) {
                     store4<NT>(p.avg + e, make_float4(o[0], o[1], o[2], o[3]));
                 } else {

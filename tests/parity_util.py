@@ -58,6 +58,30 @@ def gpu_unpack_average(plan, codes_np, s_shared):
     return avg.cpu().numpy()
 
 
+def gpu_unpack_update(plan, codes_np, s_shared, eta, w0):
+    pb = plan.packed_bytes
+    cd = []
+    for c in codes_np:
+        buf = np.zeros(pb, np.uint8)
+        buf[:c.size] = c
+        cd.append(dev(buf))
+    w = dev(w0)
+    plan.tg_unpack_update(cd, dev(s_shared), eta, w)
+    torch.cuda.synchronize()
+    return w.cpu().numpy()
+
+
+def assert_update_close(got, want, w0, avg):
+    """w' = w - eta*avg within 1e-6 of the larger of |w| and |eta*avg| (a difference has no
+    relative accuracy of its own when the two nearly cancel); where the average is 0 the weight
+    is untouched, bit for bit"""
+    assert np.array_equal(got[avg == 0], w0[avg == 0])
+    w64, want64 = w0.astype(np.float64), want.astype(np.float64)
+    err = np.abs(got.astype(np.float64) - want64)
+    scale = np.maximum(np.abs(w64), np.abs(want64 - w64))
+    assert np.all(err <= REL * scale), float((err / np.maximum(scale, 1e-300)).max())
+
+
 def assert_stats_close(got, want, grads_np, off, what):
     got = np.asarray(got, np.float64)
     want = np.asarray(want, np.float64)
@@ -112,6 +136,11 @@ def full_parity(oracle, binding, off, grads_np, c=2.5, seed=0, step=0, worker_ba
         o_avg = oracle.unpack_average(o_codes, off, o_s)
         g_avg = gpu_unpack_average(plan, o_codes, o_s)
         assert_avg_close(g_avg, o_avg)
+        # the fused update line of Algorithm 1 from the same codes
+        w0 = (np.random.default_rng(n + W).normal(size=n) * 0.05).astype(np.float32)
+        eta = 0.125 if n % 2 else 0.01
+        assert_update_close(gpu_unpack_update(plan, o_codes, o_s, eta, w0),
+                            oracle.unpack_update(o_codes, off, o_s, eta, w0), w0, o_avg)
         return dict(tau=o_tau, s_local=o_sloc, s_shared=o_s, codes=o_codes, avg=o_avg)
     finally:
         plan.close()

@@ -3,8 +3,8 @@ import numpy as np
 import pytest
 import torch
 
-from parity_util import (assert_avg_close, dev, full_parity, gpu_clip_stats, gpu_share, gpu_ternarize,
-                         gpu_unpack_average)
+from parity_util import (assert_avg_close, assert_update_close, dev, full_parity, gpu_clip_stats, gpu_share,
+                         gpu_ternarize, gpu_unpack_average, gpu_unpack_update)
 
 pytestmark = pytest.mark.gpu
 
@@ -107,6 +107,25 @@ def test_unpack_average_arbitrary_bytes(oracle, binding):
             plan.close()
 
 
+def test_unpack_update_arbitrary_bytes_and_rates(oracle, binding):
+    rng = np.random.default_rng(19)
+    off = _off([5000, 3, 4096, 2001])
+    n = int(off[-1])
+    for W, eta in ((1, 1.0), (4, 0.1), (7, 1e-3), (8, 0.0), (64, 2.5)):
+        codes = [rng.integers(0, 256, size=(n + 3) // 4, dtype=np.uint8) for _ in range(W)]
+        s = (np.abs(rng.normal(size=4)) * 1e-2 + 1e-4).astype(np.float32)
+        w0 = rng.normal(size=n).astype(np.float32)
+        plan = binding.Plan(off, W)
+        try:
+            got = gpu_unpack_update(plan, codes, s, eta, w0)
+            assert_update_close(got, oracle.unpack_update(codes, off, s, eta, w0), w0,
+                                oracle.unpack_average(codes, off, s))
+            if eta == 0.0:
+                assert np.array_equal(got, w0)
+        finally:
+            plan.close()
+
+
 def test_extreme_scalers(oracle, binding):
     """tiny (subnormal threshold products), huge and zero scalers: same decisions on both sides"""
     rng = np.random.default_rng(10)
@@ -160,5 +179,11 @@ def test_argument_errors_on_device(binding):
         with pytest.raises(binding.TgError) as e:
             plan.tg_clip_stats([g], float("nan"), t, t)
         assert e.value.status == binding.TG_ERR_INVALID_ARG
+        with pytest.raises(binding.TgError) as e:
+            plan.tg_unpack_update([codes], t, float("inf"), g)
+        assert e.value.status == binding.TG_ERR_INVALID_ARG
+        with pytest.raises(binding.TgError) as e:
+            plan.tg_unpack_update([codes], t, 0.1, g[1:])
+        assert e.value.status == binding.TG_ERR_ALIGNMENT
     finally:
         plan.close()

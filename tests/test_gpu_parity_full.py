@@ -11,7 +11,7 @@ import numpy as np
 import pytest
 import torch
 
-from parity_util import REL, assert_stats_close, dev
+from parity_util import REL, assert_stats_close, assert_update_close, dev
 
 pytestmark = pytest.mark.gpu
 
@@ -97,6 +97,14 @@ def _full_config(oracle, binding, wl):
         torch.cuda.synchronize()
         o_avg = oracle.unpack_average(o_codes, off, o_s)
         _avg_close_chunked(avg_g, o_avg)
+        del avg_g
+        # ---- fused decode + update from the same codes ----
+        w0 = torch.randn(n, dtype=torch.float32, device="cuda", generator=torch.Generator("cuda").manual_seed(5)) * 0.05
+        w0_host = w0.cpu().numpy()
+        plan.tg_unpack_update(cd, dev(o_s), 0.01, w0)
+        torch.cuda.synchronize()
+        o_w = oracle.unpack_update(o_codes, off, o_s, 0.01, w0_host)
+        assert_update_close(w0.cpu().numpy(), o_w, w0_host, o_avg)
         plan.close()
     finally:
         oracle.set_threads(1)

@@ -63,6 +63,8 @@ def lib() -> ctypes.CDLL:
         L.tgo_unpack_update.argtypes = [ctypes.POINTER(c_u8), ctypes.c_int, ctypes.c_int64, c_i64, c_f,
                                         ctypes.c_float, c_f]
         L.tgo_unpack_update.restype = None
+        L.tgo_average_float.argtypes = [ctypes.POINTER(c_f), ctypes.c_int, ctypes.c_int64, c_f]
+        L.tgo_average_float.restype = None
         _lib = L
     return _lib
 
@@ -183,3 +185,15 @@ def unpack_update(codes_list, off, s_shared, eta, weights):
     assert w.size == n
     lib().tgo_unpack_update(arr, W, L, op, sp, np.float32(eta), _f32(w)[1])
     return w
+
+
+def average_float(grads_list):
+    """plain fp32 average of W float32 arrays [n] (layers that are not ternarized)"""
+    keep = [np.ascontiguousarray(g, dtype=np.float32) for g in grads_list]
+    n = keep[0].size
+    assert all(g.size == n for g in keep)
+    fp = ctypes.POINTER(ctypes.c_float)
+    arr = (fp * len(keep))(*[g.ctypes.data_as(fp) for g in keep])
+    avg = np.empty(n, np.float32)
+    lib().tgo_average_float(arr, len(keep), n, _f32(avg)[1])
+    return avg

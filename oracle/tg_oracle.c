@@ -177,3 +177,12 @@ void tgo_unpack_update(const uint8_t* const* codes, int n_workers, int64_t n_lay
         weights[e] = (float)((double)weights[e] - (double)eta * avg);
     }
 }
+
+void tgo_average_float(const float* const* grads, int n_workers, int64_t n, float* avg) {
+    #pragma omp parallel for num_threads(g_threads) schedule(static)
+    for (int64_t e = 0; e < n; ++e) {
+        double sum = 0.0;
+        for (int w = 0; w < n_workers; ++w) sum += (double)grads[w][e];
+        avg[e] = (float)(sum / (double)n_workers);
+    }
+}

@@ -95,6 +95,11 @@ void tgo_unpack_average(const uint8_t* const* codes, int n_workers, int64_t n_la
 void tgo_unpack_update(const uint8_t* const* codes, int n_workers, int64_t n_layers,
                        const int64_t* off, const float* s_shared, float eta, float* weights);
 
+/* Layers kept in floating point (Section 4.2: the last classification layer is not
+ * ternarized): the plain average avg_e = (float)( (sum_w (double)g_w[e]) / W ), summed in
+ * worker order.  grads: W host pointers to n floats; avg: [n]. */
+void tgo_average_float(const float* const* grads, int n_workers, int64_t n, float* avg);
+
 #ifdef __cplusplus
 }
 #endif

@@ -415,3 +415,18 @@ def test_terngrad_sgd_converges_on_a_convex_problem(oracle):
         codes = [oracle.ternarize_pack(g, off, st[i][0], s, seed=7, step=t, worker=i) for i, g in enumerate(grads)]
         w = oracle.unpack_update(codes, off, s, 0.5 / (1.0 + t / 50.0), w)
     assert float(np.linalg.norm(w - w_star)) < 0.05 * d0
+
+
+# --------------------------------------------------------------------------
+# Section 4.2: a layer kept in floating point is averaged as plain floats
+# --------------------------------------------------------------------------
+def test_average_float_is_numpy_mean(oracle):
+    rng = np.random.default_rng(17)
+    for W, n in ((1, 7), (2, 1000), (4, 4097), (8, 333), (64, 50)):
+        grads = [(rng.normal(size=n) * 10.0 ** rng.uniform(-6, 2)).astype(np.float32) for _ in range(W)]
+        got = oracle.average_float(grads)
+        want = np.mean(np.stack(grads).astype(np.float64), axis=0)
+        # one rounding of the fp64 mean: equal to numpy's up to the last fp64 bit of the sum
+        assert np.all(np.abs(got.astype(np.float64) - want) <= np.spacing(np.abs(want).astype(np.float32)) * 0.5000001)
+        if W == 1:
+            assert np.array_equal(got, grads[0])

@@ -156,6 +156,15 @@ tg_status tg_unpack_average(tg_plan* plan, int n_workers, const uint8_t* const* 
 tg_status tg_unpack_update(tg_plan* plan, int n_workers, const uint8_t* const* codes,
                            const float* s_shared, float eta, float* weights, void* stream);
 
+/* Layers kept in floating point.  Section 4.2 does not ternarize the last classification
+ * layer; its gradients travel as fp32 and are averaged as such:
+ *   avg[e] = (float)( (sum_w (double)grads[w][e]) / n_workers ),  e in [0, n)
+ * (fp64 sum in worker order, one rounding).  Needs no plan: the caller builds the plan over the
+ * ternarized layers only and hands the float layers' slice of each flat buffer to this call.
+ *   grads  host array of n_workers dev pointers, each to n fp32, 16-byte aligned
+ *   avg    dev [n] fp32 out, 16-byte aligned */
+tg_status tg_average_float(int n_workers, int64_t n, const float* const* grads, float* avg, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

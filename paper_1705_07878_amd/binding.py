@@ -61,6 +61,8 @@ lib.tg_unpack_average.argtypes = [_vp, ctypes.c_int, _pp, _vp, _vp, _vp]
 lib.tg_unpack_average.restype = ctypes.c_int
 lib.tg_unpack_update.argtypes = [_vp, ctypes.c_int, _pp, _vp, ctypes.c_float, _vp, _vp]
 lib.tg_unpack_update.restype = ctypes.c_int
+lib.tg_average_float.argtypes = [ctypes.c_int, _i64, _pp, _vp, _vp]
+lib.tg_average_float.restype = ctypes.c_int
 
 
 class TgError(RuntimeError):
@@ -123,6 +125,11 @@ def tg_describe_tables(offsets):
                                   ctypes.byref(ce), ctypes.byref(ns),
                                   seg.ctypes.data_as(ctypes.POINTER(_i64)), seg.shape[0]), "tg_describe_tables")
     return {"tile_elems": te.value, "tile_layer": tl, "chunk_elems": ce.value, "segments": seg}
+
+
+def tg_average_float(grads: Sequence, n: int, avg, stream=None):
+    gp, _keep = _ptr_array(grads)
+    _check(lib.tg_average_float(len(grads), int(n), gp, _ptr(avg), _stream(stream)), "tg_average_float")
 
 
 class Plan:

@@ -11,6 +11,7 @@
 #include <new>
 #include <vector>
 
+#include "tg_float.hpp"
 #include "tg_stats.hpp"
 #include "tg_ternarize.hpp"
 #include "tg_unpack.hpp"
@@ -339,6 +340,27 @@ tg_status tg_unpack_update(tg_plan* p, int n_workers, const uint8_t* const* code
                            const float* s_shared, float eta, float* weights, void* stream) {
     if (std::isnan(eta) || std::isinf(eta)) return TG_ERR_INVALID_ARG;
     return launch_unpack(p, n_workers, codes, s_shared, weights, true, eta, stream);
+}
+
+tg_status tg_average_float(int n_workers, int64_t n, const float* const* grads, float* avg, void* stream) {
+    if (n_workers < 1 || n < 1 || grads == nullptr || avg == nullptr) return TG_ERR_INVALID_ARG;
+    if (n_workers > TG_MAX_WORKERS) return TG_ERR_TOO_MANY_WORKERS;
+    tg::FloatAvgArgs a{};
+    for (int w = 0; w < n_workers; ++w) {
+        if (grads[w] == nullptr) return TG_ERR_INVALID_ARG;
+        if (!aligned(grads[w], 16)) return TG_ERR_ALIGNMENT;
+        a.grads[w] = grads[w];
+    }
+    if (!aligned(avg, 16)) return TG_ERR_ALIGNMENT;
+    a.avg = avg;
+    a.n = n;
+    a.n_workers = n_workers;
+    const int64_t threads = (n + 3) / 4;
+    const int64_t blocks = (threads + tg::kBlock - 1) / tg::kBlock;
+    if (blocks > 0x7FFFFFFF) return TG_ERR_INVALID_ARG;
+    hipLaunchKernelGGL(tg::average_float_kernel, dim3((unsigned)blocks), dim3(tg::kBlock), 0, (hipStream_t)stream, a);
+    if (!hip_ok(hipGetLastError())) return TG_ERR_HIP;
+    return TG_OK;
 }
 
 }  // extern "C"

@@ -126,6 +126,19 @@ def test_unpack_update_arbitrary_bytes_and_rates(oracle, binding):
             plan.close()
 
 
+def test_average_float_layers(oracle, binding):
+    """Section 4.2: a layer kept in fp32 is averaged as floats; bit-exact (fp64 sum, one rounding)"""
+    rng = np.random.default_rng(21)
+    for W, n in ((1, 5), (2, 1024), (3, 4099), (4, 4_096_000), (8, 100_003), (64, 2050)):
+        grads = [(rng.normal(size=n) * 10.0 ** rng.uniform(-5, 1)).astype(np.float32) for _ in range(W)]
+        out = torch.full((n,), float("nan"), dtype=torch.float32, device="cuda")
+        binding.tg_average_float([dev(g) for g in grads], n, out)
+        torch.cuda.synchronize()
+        assert np.array_equal(out.cpu().numpy(), oracle.average_float(grads))
+    with pytest.raises(binding.TgError):
+        binding.tg_average_float([out[1:]], 4, out)
+
+
 def test_extreme_scalers(oracle, binding):
     """tiny (subnormal threshold products), huge and zero scalers: same decisions on both sides"""
     rng = np.random.default_rng(10)

@@ -65,6 +65,10 @@ def lib() -> ctypes.CDLL:
         L.tgo_unpack_update.restype = None
         L.tgo_average_float.argtypes = [ctypes.POINTER(c_f), ctypes.c_int, ctypes.c_int64, c_f]
         L.tgo_average_float.restype = None
+        L.tgo_sum_pack.argtypes = [ctypes.POINTER(c_u8), ctypes.c_int, ctypes.c_int64, ctypes.c_int, c_u8]
+        L.tgo_sum_pack.restype = None
+        L.tgo_decode_sum.argtypes = [c_u8, ctypes.c_int, ctypes.c_int, ctypes.c_int64, c_i64, c_f, c_f]
+        L.tgo_decode_sum.restype = None
         _lib = L
     return _lib
 
@@ -196,4 +200,31 @@ def average_float(grads_list):
     arr = (fp * len(keep))(*[g.ctypes.data_as(fp) for g in keep])
     avg = np.empty(n, np.float32)
     lib().tgo_average_float(arr, len(keep), n, _f32(avg)[1])
+    return avg
+
+
+def sum_pack(codes_list, n: int, bits: int):
+    """-> uint8 [ceil(n*bits/8)]: k = sum of the workers' ternary values in `bits`-wide fields"""
+    assert bits in (4, 8)
+    keep = [np.ascontiguousarray(c, dtype=np.uint8) for c in codes_list]
+    for c in keep:
+        assert c.size >= (n + 3) // 4
+    u8p = ctypes.POINTER(ctypes.c_uint8)
+    arr = (u8p * len(keep))(*[c.ctypes.data_as(u8p) for c in keep])
+    out = np.zeros((n * bits + 7) // 8, np.uint8)
+    lib().tgo_sum_pack(arr, len(keep), int(n), int(bits), out.ctypes.data_as(u8p))
+    return out
+
+
+def decode_sum(ksum, bits: int, n_workers: int, off, s_shared):
+    off = _check_offsets(off)
+    _, op = _i64(off)
+    L = off.size - 1
+    n = int(off[-1])
+    ksum = np.ascontiguousarray(ksum, dtype=np.uint8)
+    assert bits in (4, 8) and ksum.size >= (n * bits + 7) // 8
+    s_shared, sp = _f32(s_shared)
+    avg = np.empty(n, np.float32)
+    lib().tgo_decode_sum(ksum.ctypes.data_as(ctypes.POINTER(ctypes.c_uint8)), int(bits), int(n_workers), L, op, sp,
+                         _f32(avg)[1])
     return avg

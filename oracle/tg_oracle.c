@@ -186,3 +186,34 @@ void tgo_average_float(const float* const* grads, int n_workers, int64_t n, floa
         avg[e] = (float)(sum / (double)n_workers);
     }
 }
+
+void tgo_sum_pack(const uint8_t* const* codes, int n_workers, int64_t n, int bits, uint8_t* ksum) {
+    const int64_t n_bytes = (n * bits + 7) / 8;
+    for (int64_t i = 0; i < n_bytes; ++i) ksum[i] = 0;
+    for (int64_t e = 0; e < n; ++e) {
+        long k = 0;
+        for (int w = 0; w < n_workers; ++w) k += tgo_code_at(codes[w], e);
+        if (bits == 8) {
+            ksum[e] = (uint8_t)(k & 0xFF);
+        } else {
+            ksum[e >> 1] |= (uint8_t)((k & 0xF) << (4 * (e & 1)));
+        }
+    }
+}
+
+void tgo_decode_sum(const uint8_t* ksum, int bits, int n_workers, int64_t n_layers,
+                    const int64_t* off, const float* s_shared, float* avg) {
+    const int64_t n = off[n_layers];
+    #pragma omp parallel for num_threads(g_threads) schedule(static)
+    for (int64_t e = 0; e < n; ++e) {
+        const int64_t l = layer_of(e, n_layers, off);
+        int k;
+        if (bits == 8) {
+            k = (int)(int8_t)ksum[e];
+        } else {
+            const int f = (ksum[e >> 1] >> (4 * (e & 1))) & 0xF;
+            k = (f & 8) ? f - 16 : f;
+        }
+        avg[e] = (float)((double)k * (double)s_shared[l] / (double)n_workers);
+    }
+}

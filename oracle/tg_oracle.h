@@ -100,6 +100,19 @@ void tgo_unpack_update(const uint8_t* const* codes, int n_workers, int64_t n_lay
  * worker order.  grads: W host pointers to n floats; avg: [n]. */
 void tgo_average_float(const float* const* grads, int n_workers, int64_t n, float* avg);
 
+/* Server-to-worker pull with parameter localization + scaler sharing (Section 3.1): the
+ * averaged gradient has at most 2N+1 levels k * s/N, so the server sends the integer
+ * k_e = sum_w t_w(e) in a `bits`-wide two's-complement field (bits = 4 needs 2N+1 <= 16,
+ * bits = 8 serves N <= 64) instead of 32-bit floats.  Fields are stored least significant
+ * first: bits = 4 puts element e in nibble e & 1 of byte e >> 1; bits = 8 in byte e.
+ * Writes ceil(n * bits / 8) bytes; pad fields are 0.  Only the low `bits` bits of k are kept. */
+void tgo_sum_pack(const uint8_t* const* codes, int n_workers, int64_t n, int bits, uint8_t* ksum);
+
+/* The worker's side of that pull: avg_e = (float)((double)k_e * s_shared_l / W), k_e the
+ * sign-extended field.  Same result as tgo_unpack_average on the codes the sums came from. */
+void tgo_decode_sum(const uint8_t* ksum, int bits, int n_workers, int64_t n_layers,
+                    const int64_t* off, const float* s_shared, float* avg);
+
 #ifdef __cplusplus
 }
 #endif

@@ -430,3 +430,31 @@ def test_average_float_is_numpy_mean(oracle):
         assert np.all(np.abs(got.astype(np.float64) - want) <= np.spacing(np.abs(want).astype(np.float32)) * 0.5000001)
         if W == 1:
             assert np.array_equal(got, grads[0])
+
+
+# --------------------------------------------------------------------------
+# Section 3.1, server-to-worker: the average travels as the integer k (<= 2N+1 levels)
+# --------------------------------------------------------------------------
+def test_sum_pack_fields_and_decode_roundtrip(oracle):
+    rng = np.random.default_rng(18)
+    sizes = [5, 64, 1, 131]
+    off = np.concatenate([[0], np.cumsum(sizes)])
+    n = int(off[-1])
+    for W, bits in ((1, 4), (2, 4), (4, 4), (7, 4), (4, 8), (8, 8), (64, 8)):
+        assert 2 * W + 1 <= 2 ** bits
+        assert bits >= math.log2(1 + 2 * W)            # the paper's bound 32 / log2(1 + 2N)
+        ts = [rng.integers(-1, 2, size=n) for _ in range(W)]
+        codes = [_forced(oracle, t) for t in ts]
+        k = np.sum(ts, axis=0)
+        packed = oracle.sum_pack(codes, n, bits)
+        assert packed.size == (n * bits + 7) // 8        # 32 / bits times smaller than fp32
+        if bits == 8:
+            got = packed.view(np.int8).astype(np.int64)[:n]
+        else:
+            nib = np.stack([packed & 15, packed >> 4], axis=1).reshape(-1)[:n].astype(np.int64)
+            got = np.where(nib >= 8, nib - 16, nib)
+            if n % 2:
+                assert packed[-1] >> 4 == 0               # pad field
+        assert np.array_equal(got, k)
+        s = (np.abs(rng.normal(size=len(sizes))) + 0.1).astype(np.float32)
+        assert np.array_equal(oracle.decode_sum(packed, bits, W, off, s), oracle.unpack_average(codes, off, s))

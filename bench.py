@@ -151,6 +151,24 @@ def main():
                                            "pct_hbm_peak": round(100 * upd_gbs / HBM_PEAK_GBS, 1)}
     del weights
 
+    # Section 3.1 server-to-worker pull (not part of the timed step): the average as k in narrow fields
+    bits = 4 if W <= 7 else 8
+    ksum = torch.empty((plan.tg_sum_bytes(bits),), dtype=torch.uint8, device="cuda")
+    for nm, fn, nbytes in (("unpack_sum_pack", lambda: plan.tg_unpack_sum_pack(codes, bits, ksum), 0.25 * W + bits / 8.0),
+                           ("decode_sum", lambda: plan.tg_decode_sum(W, ksum, bits, s_shared, avg), bits / 8.0 + 4.0)):
+        for _ in range(2):
+            fn()
+        e0.record(stream)
+        for _ in range(reps):
+            fn()
+        e1.record(stream)
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / reps
+        gbs = n * nbytes / (ms * 1e-3) / 1e9
+        kern["%s %d-bit (not in step)" % (nm, bits)] = {"ms": round(ms, 4), "algorithmic_GBps": round(gbs, 1),
+                                                        "pct_hbm_peak": round(100 * gbs / HBM_PEAK_GBS, 1)}
+    del ksum
+
     # Section 4.2 variant (not part of the timed step): plain fp32 average, as used for a layer that is
     # kept in floating point; timed here over the whole flat buffer to get a bandwidth figure
     favg = torch.empty((n,), dtype=torch.float32, device="cuda")

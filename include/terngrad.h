@@ -156,6 +156,26 @@ tg_status tg_unpack_average(tg_plan* plan, int n_workers, const uint8_t* const* 
 tg_status tg_unpack_update(tg_plan* plan, int n_workers, const uint8_t* const* codes,
                            const float* s_shared, float eta, float* weights, void* stream);
 
+/* Server-to-worker pull (Section 3.1): with parameter localization and a shared scaler the
+ * averaged gradient has at most 2N+1 levels k * s/N, so it can travel as the integer
+ * k = sum_w t_w in a narrow field instead of a 32-bit float (the paper's 32 / log2(1+2N)).
+ * Fields are `bits`-wide two's complement, least significant first: bits = 4 (needs
+ * n_workers <= 7) puts element e in nibble e & 1 of byte e >> 1; bits = 8 puts it in byte e.
+ * A buffer holds tg_sum_bytes(plan, bits) = ceil(n*bits/8) rounded up to 16 bytes, 16-byte
+ * aligned; pad fields are written as 0.  Codes must be valid (no 10): only the low `bits`
+ * bits of k are kept. */
+int64_t tg_sum_bytes(const tg_plan* plan, int bits);   /* -1 for a NULL plan or bits not 4 / 8 */
+
+/* The server's side: decode the N code buffers, sum, write k.  ksum: dev, out. */
+tg_status tg_unpack_sum_pack(tg_plan* plan, int n_workers, const uint8_t* const* codes, int bits,
+                             uint8_t* ksum, void* stream);
+
+/* The worker's side: avg[e] = k[e] * (s_shared[layer(e)] / n_workers), exactly the value
+ * tg_unpack_average produces from the codes the sums came from.  n_workers is the N the sums
+ * were formed over (it need not fit the plan's max_workers: no per-worker buffer is touched). */
+tg_status tg_decode_sum(tg_plan* plan, int n_workers, const uint8_t* ksum, int bits,
+                        const float* s_shared, float* avg, void* stream);
+
 /* Layers kept in floating point.  Section 4.2 does not ternarize the last classification
  * layer; its gradients travel as fp32 and are averaged as such:
  *   avg[e] = (float)( (sum_w (double)grads[w][e]) / n_workers ),  e in [0, n)

@@ -61,6 +61,12 @@ lib.tg_unpack_average.argtypes = [_vp, ctypes.c_int, _pp, _vp, _vp, _vp]
 lib.tg_unpack_average.restype = ctypes.c_int
 lib.tg_unpack_update.argtypes = [_vp, ctypes.c_int, _pp, _vp, ctypes.c_float, _vp, _vp]
 lib.tg_unpack_update.restype = ctypes.c_int
+lib.tg_sum_bytes.argtypes = [_vp, ctypes.c_int]
+lib.tg_sum_bytes.restype = _i64
+lib.tg_unpack_sum_pack.argtypes = [_vp, ctypes.c_int, _pp, ctypes.c_int, _vp, _vp]
+lib.tg_unpack_sum_pack.restype = ctypes.c_int
+lib.tg_decode_sum.argtypes = [_vp, ctypes.c_int, _vp, ctypes.c_int, _vp, _vp, _vp]
+lib.tg_decode_sum.restype = ctypes.c_int
 lib.tg_average_float.argtypes = [ctypes.c_int, _i64, _pp, _vp, _vp]
 lib.tg_average_float.restype = ctypes.c_int
 
@@ -197,3 +203,15 @@ class Plan:
         cp, _k = _ptr_array(codes)
         _check(lib.tg_unpack_update(self._h, len(codes), cp, _ptr(s_shared), float(eta), _ptr(weights),
                                     _stream(stream)), "tg_unpack_update")
+
+    def tg_sum_bytes(self, bits: int) -> int:
+        return int(lib.tg_sum_bytes(self._h, int(bits)))
+
+    def tg_unpack_sum_pack(self, codes: Sequence, bits: int, ksum, stream=None):
+        cp, _k = _ptr_array(codes)
+        _check(lib.tg_unpack_sum_pack(self._h, len(codes), cp, int(bits), _ptr(ksum), _stream(stream)),
+               "tg_unpack_sum_pack")
+
+    def tg_decode_sum(self, n_workers: int, ksum, bits: int, s_shared, avg, stream=None):
+        _check(lib.tg_decode_sum(self._h, int(n_workers), _ptr(ksum), int(bits), _ptr(s_shared), _ptr(avg),
+                                 _stream(stream)), "tg_decode_sum")

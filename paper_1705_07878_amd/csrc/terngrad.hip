@@ -107,6 +107,37 @@ struct tg_plan {
     float* d_pmax = nullptr;
 };
 
+static int64_t sum_bytes(const tg_plan* p, int bits) { return ((p->n * bits + 7) / 8 + 15) / 16 * 16; }
+
+template <int SRC, int DST>
+static tg_status launch_unpack(const tg_plan* p, const tg::UnpackArgs& a, void* stream) {
+    const int64_t blocks = (a.n_wave_tiles + tg::kBlock / tg::kWave - 1) / (tg::kBlock / tg::kWave);
+    hipLaunchKernelGGL((tg::unpack_average_kernel<true, SRC, DST>), dim3((unsigned)blocks), dim3(tg::kBlock), 0,
+                       (hipStream_t)stream, a);
+    (void)p;
+    if (!hip_ok(hipGetLastError())) return TG_ERR_HIP;
+    return TG_OK;
+}
+
+static tg_status fill_unpack(const tg_plan* p, int n_workers, const uint8_t* const* codes, tg::UnpackArgs& a) {
+    a.off = p->d_off;
+    a.tile_layer = p->d_tile_layer;
+    a.n = p->n;
+    a.n_wave_tiles = (p->n + tg::kWaveTile - 1) / tg::kWaveTile;
+    a.packed_bytes = p->packed_bytes;
+    a.n_layers = (int32_t)p->n_layers;
+    a.n_workers = n_workers;
+    if (codes != nullptr)
+        for (int w = 0; w < n_workers; ++w) {
+            if (codes[w] == nullptr) return TG_ERR_INVALID_ARG;
+            if (!aligned(codes[w], 4)) return TG_ERR_ALIGNMENT;
+            a.codes[w] = codes[w];
+        }
+    return TG_OK;
+}
+
+static bool bits_hold(int bits, int n_workers) { return (bits == 4 && n_workers <= 7) || bits == 8; }
+
 extern "C" {
 
 const char* tg_strerror(int status) {
@@ -298,48 +329,73 @@ tg_status tg_ternarize_pack(tg_plan* p, int n_workers, uint32_t worker_base,
     return TG_OK;
 }
 
-static tg_status launch_unpack(tg_plan* p, int n_workers, const uint8_t* const* codes,
-                               const float* s_shared, float* out, bool update, float eta, void* stream) {
-    tg_status st = check_workers(p, n_workers);
-    if (st != TG_OK) return st;
-    if (codes == nullptr || s_shared == nullptr || out == nullptr) return TG_ERR_INVALID_ARG;
-    tg::UnpackArgs a{};
-    for (int w = 0; w < n_workers; ++w) {
-        if (codes[w] == nullptr) return TG_ERR_INVALID_ARG;
-        if (!aligned(codes[w], 4)) return TG_ERR_ALIGNMENT;
-        a.codes[w] = codes[w];
-    }
-    if (!aligned(s_shared, 4) || !aligned(out, 16)) return TG_ERR_ALIGNMENT;
-    a.s_shared = s_shared;
-    a.off = p->d_off;
-    a.tile_layer = p->d_tile_layer;
-    a.avg = out;
-    a.eta = eta;
-    a.n = p->n;
-    a.n_wave_tiles = (p->n + tg::kWaveTile - 1) / tg::kWaveTile;
-    a.packed_bytes = p->packed_bytes;
-    a.n_layers = (int32_t)p->n_layers;
-    a.n_workers = n_workers;
-    const int64_t blocks = (a.n_wave_tiles + tg::kBlock / tg::kWave - 1) / (tg::kBlock / tg::kWave);
-    if (update)
-        hipLaunchKernelGGL((tg::unpack_average_kernel<true, true>), dim3((unsigned)blocks), dim3(tg::kBlock), 0,
-                           (hipStream_t)stream, a);
-    else
-        hipLaunchKernelGGL((tg::unpack_average_kernel<true, false>), dim3((unsigned)blocks), dim3(tg::kBlock), 0,
-                           (hipStream_t)stream, a);
-    if (!hip_ok(hipGetLastError())) return TG_ERR_HIP;
-    return TG_OK;
-}
-
 tg_status tg_unpack_average(tg_plan* p, int n_workers, const uint8_t* const* codes,
                             const float* s_shared, float* avg, void* stream) {
-    return launch_unpack(p, n_workers, codes, s_shared, avg, false, 0.0f, stream);
+    tg_status st = check_workers(p, n_workers);
+    if (st != TG_OK) return st;
+    if (codes == nullptr || s_shared == nullptr || avg == nullptr) return TG_ERR_INVALID_ARG;
+    tg::UnpackArgs a{};
+    if ((st = fill_unpack(p, n_workers, codes, a)) != TG_OK) return st;
+    if (!aligned(s_shared, 4) || !aligned(avg, 16)) return TG_ERR_ALIGNMENT;
+    a.s_shared = s_shared;
+    a.avg = avg;
+    return launch_unpack<tg::SRC_CODES, tg::DST_AVG>(p, a, stream);
 }
 
 tg_status tg_unpack_update(tg_plan* p, int n_workers, const uint8_t* const* codes,
                            const float* s_shared, float eta, float* weights, void* stream) {
-    if (std::isnan(eta) || std::isinf(eta)) return TG_ERR_INVALID_ARG;
-    return launch_unpack(p, n_workers, codes, s_shared, weights, true, eta, stream);
+    tg_status st = check_workers(p, n_workers);
+    if (st != TG_OK) return st;
+    if (codes == nullptr || s_shared == nullptr || weights == nullptr || std::isnan(eta) || std::isinf(eta))
+        return TG_ERR_INVALID_ARG;
+    tg::UnpackArgs a{};
+    if ((st = fill_unpack(p, n_workers, codes, a)) != TG_OK) return st;
+    if (!aligned(s_shared, 4) || !aligned(weights, 16)) return TG_ERR_ALIGNMENT;
+    a.s_shared = s_shared;
+    a.avg = weights;
+    a.eta = eta;
+    return launch_unpack<tg::SRC_CODES, tg::DST_UPDATE>(p, a, stream);
+}
+
+int64_t tg_sum_bytes(const tg_plan* p, int bits) {
+    if (p == nullptr || (bits != 4 && bits != 8)) return -1;
+    return sum_bytes(p, bits);
+}
+
+tg_status tg_unpack_sum_pack(tg_plan* p, int n_workers, const uint8_t* const* codes, int bits,
+                             uint8_t* ksum, void* stream) {
+    tg_status st = check_workers(p, n_workers);
+    if (st != TG_OK) return st;
+    if (codes == nullptr || ksum == nullptr || (bits != 4 && bits != 8) || !bits_hold(bits, n_workers))
+        return TG_ERR_INVALID_ARG;
+    tg::UnpackArgs a{};
+    if ((st = fill_unpack(p, n_workers, codes, a)) != TG_OK) return st;
+    if (!aligned(ksum, 16)) return TG_ERR_ALIGNMENT;
+    a.ksum_out = ksum;
+    a.ksum_bytes = sum_bytes(p, bits);
+    // the tiles must cover the pad fields too
+    a.n_wave_tiles = (a.ksum_bytes * 8 / bits + tg::kWaveTile - 1) / tg::kWaveTile;
+    return bits == 4 ? launch_unpack<tg::SRC_CODES, tg::DST_K4>(p, a, stream)
+                     : launch_unpack<tg::SRC_CODES, tg::DST_K8>(p, a, stream);
+}
+
+tg_status tg_decode_sum(tg_plan* p, int n_workers, const uint8_t* ksum, int bits,
+                        const float* s_shared, float* avg, void* stream) {
+    if (p == nullptr || n_workers < 1) return TG_ERR_INVALID_ARG;
+    if (n_workers > TG_MAX_WORKERS) return TG_ERR_TOO_MANY_WORKERS;
+    if (ksum == nullptr || s_shared == nullptr || avg == nullptr || (bits != 4 && bits != 8) ||
+        !bits_hold(bits, n_workers))
+        return TG_ERR_INVALID_ARG;
+    tg::UnpackArgs a{};
+    tg_status st = fill_unpack(p, n_workers, nullptr, a);
+    if (st != TG_OK) return st;
+    if (!aligned(ksum, 16) || !aligned(s_shared, 4) || !aligned(avg, 16)) return TG_ERR_ALIGNMENT;
+    a.ksum_in = ksum;
+    a.ksum_bytes = sum_bytes(p, bits);
+    a.s_shared = s_shared;
+    a.avg = avg;
+    return bits == 4 ? launch_unpack<tg::SRC_K4, tg::DST_AVG>(p, a, stream)
+                     : launch_unpack<tg::SRC_K8, tg::DST_AVG>(p, a, stream);
 }
 
 tg_status tg_average_float(int n_workers, int64_t n, const float* const* grads, float* avg, void* stream) {

@@ -25,6 +25,9 @@ struct UnpackArgs {
     const int32_t* tile_layer;
     float* avg;                 // [n]: the average (out), or the weights (in/out) when updating
     float eta;                  // learning rate of the fused update
+    const uint8_t* ksum_in;     // packed sums k (4- or 8-bit fields), when they are the source
+    uint8_t* ksum_out;          // packed sums k, when they are the sink
+    int64_t ksum_bytes;         // size of that buffer: ceil(n * bits / 8) rounded up to 16
     int64_t n;
     int64_t n_wave_tiles;       // ceil(n / 1024)
     int64_t packed_bytes;
@@ -95,10 +98,30 @@ __device__ __forceinline__ float4 apply4(const float4 w, const float4 a, const f
                        __builtin_fmaf(-eta, a.z, w.z), __builtin_fmaf(-eta, a.w, w.w));
 }
 
-// UPDATE = false: avg[e] = k * (s/W)                 (Algorithm 1, server line)
-// UPDATE = true:  w[e]  = w[e] - eta * k * (s/W)     (server line fused with the update line:
-//                 the average is never written to or re-read from HBM)
-template <bool NT, bool UPDATE>
+// Where the per-element integer k comes from and where it goes.
+//   source  SRC_CODES: k = sum_w t_w, from the W workers' 2-bit code buffers
+//           SRC_K4 / SRC_K8: k read from a buffer of 4- / 8-bit two's-complement fields
+//   sink    DST_AVG:    avg[e] = k * (s/W)               (Algorithm 1, server line)
+//           DST_UPDATE: w[e]  -= eta * k * (s/W)          (server line fused with the update line:
+//                       the average is never written to or re-read from HBM)
+//           DST_K4 / DST_K8: k itself in 4- / 8-bit fields (the server-to-worker pull of
+//                       Section 3.1: at most 2N+1 levels instead of 32-bit floats)
+enum { SRC_CODES = 0, SRC_K4 = 1, SRC_K8 = 2 };
+enum { DST_AVG = 0, DST_UPDATE = 1, DST_K4 = 2, DST_K8 = 3 };
+
+// sign-extend the low nibble of every byte: bit 3 set -> bits 4..7 set (0x08 * 30 = 0xF0)
+__device__ __forceinline__ uint32_t sext_nibbles(const uint32_t y) {
+    return y | ((y & 0x08080808u) * 30u);
+}
+
+// low nibbles of the 8 bytes of (d0, d1) -> 8 consecutive 4-bit fields
+__device__ __forceinline__ uint32_t pack_nibbles(const uint32_t d0, const uint32_t d1) {
+    const uint32_t y0 = d0 & 0x0F0F0F0Fu, y1 = d1 & 0x0F0F0F0Fu;
+    const uint32_t t0 = y0 | (y0 >> 4), t1 = y1 | (y1 >> 4);     // bytes 0 and 2 hold two fields each
+    return __builtin_amdgcn_perm(t1, t0, 0x06040200u);
+}
+
+template <bool NT, int SRC, int DST>
 __global__ void __launch_bounds__(kBlock) unpack_average_kernel(const UnpackArgs p) {
     __shared__ uint32_t lds[kBlock / kWave][kWaveTile / 4];   // 1 KiB per wave
 
@@ -106,23 +129,26 @@ __global__ void __launch_bounds__(kBlock) unpack_average_kernel(const UnpackArgs
     const int wave = wave_uniform(threadIdx.x >> 6);
     const int W = p.n_workers;
     const float fW = (float)W;
-    const uint32_t bias = (uint32_t)(128 - 2 * W) * 0x01010101u;
+    constexpr bool UPDATE = DST == DST_UPDATE;
 
-    {
-        // one tile per wave (see ternarize_pack_kernel)
-        const int64_t wt = (int64_t)blockIdx.x * (kBlock / kWave) + wave;
-        if (wt >= p.n_wave_tiles) return;
-        const int64_t e0 = wt * kWaveTile;
+    // one tile per wave (see ternarize_pack_kernel)
+    const int64_t wt = (int64_t)blockIdx.x * (kBlock / kWave) + wave;
+    if (wt >= p.n_wave_tiles) return;
+    const int64_t e0 = wt * kWaveTile;
+    const bool full = e0 + kWaveTile <= p.n;
+    float4 wv[4];
+    if (UPDATE && full) {
+        // the weights depend on nothing: issue their loads first
+#pragma unroll
+        for (int k = 0; k < 4; ++k) wv[k] = load_stream(p.avg + e0 + 4 * lane + 256 * k);
+    }
+
+    // ---- D[m] = k of the lane's elements 16*lane + 4m .. 4m+3, one signed byte each ----
+    uint32_t D[4];
+    if (SRC == SRC_CODES) {
         const int64_t byte0 = (e0 >> 2) + 4 * lane;
         const bool in_codes = byte0 < p.packed_bytes;      // false only in the ragged last tile
-        const bool full = e0 + kWaveTile <= p.n;
-        float4 wv[4];
-        if (UPDATE && full) {
-            // the weights depend on nothing: issue their loads first
-#pragma unroll
-            for (int k = 0; k < 4; ++k) wv[k] = load_stream(p.avg + e0 + 4 * lane + 256 * k);
-        }
-
+        const uint32_t bias = (uint32_t)(128 - 2 * W) * 0x01010101u;
         Byt acc = {bias, bias, bias, bias};
         for (int w0 = 0; w0 < W; w0 += 5) {
             // up to five workers per 4-bit counter: 5 * 3 = 15
@@ -140,57 +166,87 @@ __global__ void __launch_bounds__(kBlock) unpack_average_kernel(const UnpackArgs
         }
         // counters hold 128 + k: flip bit 7 to get k as int8
         acc.e_lo ^= 0x80808080u; acc.o_lo ^= 0x80808080u; acc.e_hi ^= 0x80808080u; acc.o_hi ^= 0x80808080u;
-        uint32_t D[4];
         gather_bytes(D, acc);
+        if (!in_codes) D[0] = D[1] = D[2] = D[3] = 0u;
+    } else if (SRC == SRC_K8) {
+        const int64_t byte0 = e0 + 16 * lane;
+        uint4 q = make_uint4(0u, 0u, 0u, 0u);
+        if (byte0 < p.ksum_bytes) q = *reinterpret_cast<const uint4*>(p.ksum_in + byte0);
+        D[0] = q.x, D[1] = q.y, D[2] = q.z, D[3] = q.w;
+    } else {
+        const int64_t byte0 = (e0 >> 1) + 8 * lane;
+        uint2 q = make_uint2(0u, 0u);
+        if (byte0 < p.ksum_bytes) q = *reinterpret_cast<const uint2*>(p.ksum_in + byte0);
+        // nibble j of q.x / q.y = element j / 8 + j
+        const uint32_t lo0 = q.x & 0x0F0F0F0Fu, hi0 = (q.x >> 4) & 0x0F0F0F0Fu;
+        const uint32_t lo1 = q.y & 0x0F0F0F0Fu, hi1 = (q.y >> 4) & 0x0F0F0F0Fu;
+        D[0] = sext_nibbles(__builtin_amdgcn_perm(hi0, lo0, 0x05010400u));
+        D[1] = sext_nibbles(__builtin_amdgcn_perm(hi0, lo0, 0x07030602u));
+        D[2] = sext_nibbles(__builtin_amdgcn_perm(hi1, lo1, 0x05010400u));
+        D[3] = sext_nibbles(__builtin_amdgcn_perm(hi1, lo1, 0x07030602u));
+    }
 
-        uint32_t* row = lds[wave];
-        *reinterpret_cast<uint4*>(row + 4 * lane) = make_uint4(D[0], D[1], D[2], D[3]);
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-        __builtin_amdgcn_wave_barrier();
-        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    // ---- sinks that keep k: the lane's 16 fields are already consecutive in memory ----
+    if (DST == DST_K8) {
+        const int64_t byte0 = e0 + 16 * lane;
+        if (byte0 < p.ksum_bytes) *reinterpret_cast<uint4*>(p.ksum_out + byte0) = make_uint4(D[0], D[1], D[2], D[3]);
+        return;
+    }
+    if (DST == DST_K4) {
+        const int64_t byte0 = (e0 >> 1) + 8 * lane;
+        if (byte0 < p.ksum_bytes)
+            *reinterpret_cast<uint2*>(p.ksum_out + byte0) = make_uint2(pack_nibbles(D[0], D[1]), pack_nibbles(D[2], D[3]));
+        return;
+    }
 
-        const int l0 = layer_from(p.off, p.n_layers, p.tile_layer[e0 >> kTileShift], e0);
-        const bool one_layer = p.off[l0 + 1] >= e0 + kWaveTile || l0 + 1 >= p.n_layers;
-        if (one_layer && full) {
-            const float sc = p.s_shared[l0] / fW;
-            float* dst = p.avg + e0 + 4 * lane;
+    // ---- sinks that scale: transpose the bytes so that every lane stores whole float4s ----
+    uint32_t* row = lds[wave];
+    *reinterpret_cast<uint4*>(row + 4 * lane) = make_uint4(D[0], D[1], D[2], D[3]);
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+
+    const int l0 = layer_from(p.off, p.n_layers, p.tile_layer[e0 >> kTileShift], e0);
+    const bool one_layer = p.off[l0 + 1] >= e0 + kWaveTile || l0 + 1 >= p.n_layers;
+    if (one_layer && full) {
+        const float sc = p.s_shared[l0] / fW;
+        float* dst = p.avg + e0 + 4 * lane;
 #pragma unroll
-            for (int k = 0; k < 4; ++k) {
-                float4 o = scale4(row[64 * k + lane], sc);
-                if (UPDATE) o = apply4(wv[k], o, p.eta);
-                store4<NT>(dst + 256 * k, o);
+        for (int k = 0; k < 4; ++k) {
+            float4 o = scale4(row[64 * k + lane], sc);
+            if (UPDATE) o = apply4(wv[k], o, p.eta);
+            store4<NT>(dst + 256 * k, o);
+        }
+    } else {
+        // layers change inside the tile, or the tile is ragged: the layer of the element at
+        // tile position x is l0 + #{ j > l0 : off[j] - e0 <= x } (one scalar pass over the
+        // boundaries inside the tile); one scale per element
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const int x0 = 256 * k + 4 * lane;
+            const int64_t e = e0 + x0;
+            int l[4] = {l0, l0, l0, l0};
+            for (int j = l0 + 1; j < p.n_layers; ++j) {
+                const int64_t rel = p.off[j] - e0;
+                if (rel >= kWaveTile) break;
+                const int r = (int)rel;
+#pragma unroll
+                for (int i = 0; i < 4; ++i) l[i] += (x0 + i >= r) ? 1 : 0;
             }
-        } else {
-            // layers change inside the tile, or the tile is ragged: the layer of the element at
-            // tile position x is l0 + #{ j > l0 : off[j] - e0 <= x } (one scalar pass over the
-            // boundaries inside the tile); one scale per element
+            const int d = (int)row[64 * k + lane];
+            const int kk[4] = {(int)(int8_t)d, (int)(int8_t)(d >> 8), (int)(int8_t)(d >> 16), d >> 24};
+            float o[4];
 #pragma unroll
-            for (int k = 0; k < 4; ++k) {
-                const int x0 = 256 * k + 4 * lane;
-                const int64_t e = e0 + x0;
-                int l[4] = {l0, l0, l0, l0};
-                for (int j = l0 + 1; j < p.n_layers; ++j) {
-                    const int64_t rel = p.off[j] - e0;
-                    if (rel >= kWaveTile) break;
-                    const int r = (int)rel;
+            for (int i = 0; i < 4; ++i) {
+                o[i] = (float)kk[i] * (p.s_shared[l[i]] / fW);
+                if (UPDATE && e + i < p.n) o[i] = __builtin_fmaf(-p.eta, o[i], p.avg[e + i]);
+            }
+            if (e + 3 < p.n) {
+                store4<NT>(p.avg + e, make_float4(o[0], o[1], o[2], o[3]));
+            } else {
 #pragma unroll
-                    for (int i = 0; i < 4; ++i) l[i] += (x0 + i >= r) ? 1 : 0;
-                }
-                const int d = (int)row[64 * k + lane];
-                const int kk[4] = {(int)(int8_t)d, (int)(int8_t)(d >> 8), (int)(int8_t)(d >> 16), d >> 24};
-                float o[4];
-#pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    o[i] = (float)kk[i] * (p.s_shared[l[i]] / fW);
-                    if (UPDATE && e + i < p.n) o[i] = __builtin_fmaf(-p.eta, o[i], p.avg[e + i]);
-                }
-                if (e + 3 < p.n) {
-                    store4<NT>(p.avg + e, make_float4(o[0], o[1], o[2], o[3]));
-                } else {
-#pragma unroll
-                    for (int i = 0; i < 4; ++i)
-                        if (e + i < p.n) p.avg[e + i] = o[i];
-                }
+                for (int i = 0; i < 4; ++i)
+                    if (e + i < p.n) p.avg[e + i] = o[i];
             }
         }
     }

@@ -139,6 +139,59 @@ def test_average_float_layers(oracle, binding):
         binding.tg_average_float([out[1:]], 4, out)
 
 
+@pytest.mark.parametrize("W,bits", [(1, 4), (2, 4), (4, 4), (7, 4), (4, 8), (8, 8), (11, 8), (64, 8)])
+def test_sum_pack_and_decode_sum(oracle, binding, W, bits):
+    """Section 3.1 server-to-worker pull: k in narrow fields; bit-exact both ways, and the decoded
+    average is bit-identical to tg_unpack_average on the same codes"""
+    rng = np.random.default_rng(100 * W + bits)
+    for sizes in ([37], [4096, 1, 3000, 5], [20000, 1029], [16384 * 2]):
+        off = _off(sizes)
+        n = int(off[-1])
+        L = len(sizes)
+        grads = _grads(rng, off, W)
+        st = [oracle.clip_stats(g, off, 2.5) for g in grads]
+        s = oracle.share_scalers(np.stack([x[1] for x in st]))
+        codes = [oracle.ternarize_pack(g, off, st[w][0], s, 3, 4, w) for w, g in enumerate(grads)]
+        plan = binding.Plan(off, W)
+        try:
+            cd = []
+            for c in codes:
+                buf = np.zeros(plan.packed_bytes, np.uint8)
+                buf[:c.size] = c
+                cd.append(dev(buf))
+            nbytes = plan.tg_sum_bytes(bits)
+            assert nbytes == ((n * bits + 7) // 8 + 15) // 16 * 16
+            ksum = torch.full((nbytes,), 0xEE, dtype=torch.uint8, device="cuda")
+            plan.tg_unpack_sum_pack(cd, bits, ksum)
+            torch.cuda.synchronize()
+            want = oracle.sum_pack(codes, n, bits)
+            got = ksum.cpu().numpy()
+            assert np.array_equal(got[:want.size], want) and not got[want.size:].any()
+            avg = torch.full((n,), float("nan"), dtype=torch.float32, device="cuda")
+            plan.tg_decode_sum(W, dev(np.concatenate([want, np.zeros(nbytes - want.size, np.uint8)])), bits, dev(s), avg)
+            torch.cuda.synchronize()
+            assert_avg_close(avg.cpu().numpy(), oracle.decode_sum(want, bits, W, off, s))
+            assert np.array_equal(avg.cpu().numpy(), gpu_unpack_average(plan, codes, s))
+        finally:
+            plan.close()
+
+
+def test_sum_pack_rejects_fields_that_cannot_hold_the_sum(binding):
+    off = _off([100])
+    plan = binding.Plan(off, 8)
+    try:
+        c = [torch.zeros(plan.packed_bytes, dtype=torch.uint8, device="cuda")] * 8
+        k = torch.zeros(plan.tg_sum_bytes(8), dtype=torch.uint8, device="cuda")
+        with pytest.raises(binding.TgError) as e:
+            plan.tg_unpack_sum_pack(c, 4, k)              # 17 levels do not fit 4 bits
+        assert e.value.status == binding.TG_ERR_INVALID_ARG
+        with pytest.raises(binding.TgError):
+            plan.tg_unpack_sum_pack(c, 5, k)
+        assert plan.tg_sum_bytes(3) == -1
+    finally:
+        plan.close()
+
+
 def test_extreme_scalers(oracle, binding):
     """tiny (subnormal threshold products), huge and zero scalers: same decisions on both sides"""
     rng = np.random.default_rng(10)

@@ -71,6 +71,13 @@ __device__ __forceinline__ float4 load_stream(const float* p) {
     return make_float4(t.x, t.y, t.z, t.w);
 }
 
+// Dword store with the sc1 cache-policy bit (system scope: written through instead of lingering
+// in L2).  For the thin code stream that accompanies the gradient read this measured 4 % faster
+// than a plain, an sc0 or an nt store.
+__device__ __forceinline__ void store_through(uint32_t* p, uint32_t v) {
+    asm volatile("global_store_dword %0, %1, off sc1" ::"v"(p), "v"(v) : "memory");
+}
+
 // value held by the neighbouring lane (lane ^ 1), via DPP quad_perm [1,0,3,2]
 __device__ __forceinline__ uint32_t swap_adjacent(uint32_t v) {
     return (uint32_t)__builtin_amdgcn_mov_dpp((int)v, 0xB1, 0xF, 0xF, true);

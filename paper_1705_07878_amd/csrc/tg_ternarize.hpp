@@ -176,7 +176,7 @@ __global__ void __launch_bounds__(kBlock) ternarize_pack_kernel(const TernArgs p
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
     const uint32_t dw = lds[wave][lane];
     const int64_t byte0 = (e0 >> 2) + 4 * lane;
-    if (byte0 < p.packed_bytes) *reinterpret_cast<uint32_t*>(codes + byte0) = dw;
+    if (byte0 < p.packed_bytes) store_through(reinterpret_cast<uint32_t*>(codes + byte0), dw);
 }
 
 }  // namespace tg

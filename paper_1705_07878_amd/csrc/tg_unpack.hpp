@@ -9,9 +9,9 @@
 //     counters, up to five workers are added per counter, then the counters are
 //     widened to bytes.  Byte sums start at 128 - 2W, so a final XOR with 0x80
 //     leaves k = sum_w t_w as a signed byte;
-//   * the signed bytes (1 B per element) are transposed through 1 KiB of LDS
-//     per wave so that every lane converts and stores whole float4s and the
-//     wave writes 1 KiB contiguous per store instruction.
+//   * the signed bytes (1 B per element) are transposed through LDS so that every
+//     lane converts and stores whole float4s; the four waves of a workgroup write each
+//     of its four tiles together, 4 KiB contiguous per store step.
 #pragma once
 
 #include "tg_common.hpp"
@@ -121,9 +121,11 @@ __device__ __forceinline__ uint32_t pack_nibbles(const uint32_t d0, const uint32
     return __builtin_amdgcn_perm(t1, t0, 0x06040200u);
 }
 
+constexpr int kTilesPerBlock = kBlock / kWave;   // 4 tiles of 1024 elements per workgroup
+
 template <bool NT, int SRC, int DST>
 __global__ void __launch_bounds__(kBlock) unpack_average_kernel(const UnpackArgs p) {
-    __shared__ uint32_t lds[kBlock / kWave][kWaveTile / 4];   // 1 KiB per wave
+    __shared__ uint32_t lds[kTilesPerBlock][kWaveTile / 4];   // 1 KiB per tile
 
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = wave_uniform(threadIdx.x >> 6);
@@ -131,110 +133,116 @@ __global__ void __launch_bounds__(kBlock) unpack_average_kernel(const UnpackArgs
     const float fW = (float)W;
     constexpr bool UPDATE = DST == DST_UPDATE;
 
-    // one tile per wave (see ternarize_pack_kernel)
-    const int64_t wt = (int64_t)blockIdx.x * (kBlock / kWave) + wave;
-    if (wt >= p.n_wave_tiles) return;
+    // A workgroup owns 4 consecutive tiles.  Wave j sums the codes of tile j (one short-lived pass,
+    // every table lookup a scalar load); after a barrier the four waves write each tile together,
+    // wave j the j-th quarter, so that every store step of the workgroup covers 4 KiB contiguous.
+    // Measured: 6 - 10 % faster than each wave storing its own tile.
+    const int64_t tile0 = (int64_t)blockIdx.x * kTilesPerBlock;
+    const int64_t wt = tile0 + wave;
+    const bool valid = wt < p.n_wave_tiles;
     const int64_t e0 = wt * kWaveTile;
-    const bool full = e0 + kWaveTile <= p.n;
-    float4 wv[4];
-    if (UPDATE && full) {
+    const int xq = 256 * wave + 4 * lane;              // this lane's position inside any tile when storing
+
+    float4 wv[kTilesPerBlock];
+    if (UPDATE) {
         // the weights depend on nothing: issue their loads first
 #pragma unroll
-        for (int k = 0; k < 4; ++k) wv[k] = load_stream(p.avg + e0 + 4 * lane + 256 * k);
+        for (int t = 0; t < kTilesPerBlock; ++t) {
+            const int64_t e = (tile0 + t) * kWaveTile + xq;
+            if (e + 3 < p.n) wv[t] = load_stream(p.avg + e);
+        }
     }
 
-    // ---- D[m] = k of the lane's elements 16*lane + 4m .. 4m+3, one signed byte each ----
-    uint32_t D[4];
-    if (SRC == SRC_CODES) {
-        const int64_t byte0 = (e0 >> 2) + 4 * lane;
-        const bool in_codes = byte0 < p.packed_bytes;      // false only in the ragged last tile
-        const uint32_t bias = (uint32_t)(128 - 2 * W) * 0x01010101u;
-        Byt acc = {bias, bias, bias, bias};
-        for (int w0 = 0; w0 < W; w0 += 5) {
-            // up to five workers per 4-bit counter: 5 * 3 = 15
-            uint32_t x[5];
+    // ---- D[m] = k of the lane's elements 16*lane + 4m .. 4m+3 of tile `wt`, one signed byte each ----
+    uint32_t D[4] = {0u, 0u, 0u, 0u};
+    if (valid) {
+        if (SRC == SRC_CODES) {
+            const int64_t byte0 = (e0 >> 2) + 4 * lane;
+            const bool in_codes = byte0 < p.packed_bytes;      // false only in the ragged last tile
+            const uint32_t bias = (uint32_t)(128 - 2 * W) * 0x01010101u;
+            Byt acc = {bias, bias, bias, bias};
+            for (int w0 = 0; w0 < W; w0 += 5) {
+                // up to five workers per 4-bit counter: 5 * 3 = 15
+                uint32_t x[5];
 #pragma unroll
-            for (int j = 0; j < 5; ++j) {
-                x[j] = 0xAAAAAAAAu;                         // an absent worker adds t + 2 = 0
-                if (w0 + j < W && in_codes)
-                    x[j] = *reinterpret_cast<const uint32_t*>(p.codes[w0 + j] + byte0);
+                for (int j = 0; j < 5; ++j) {
+                    x[j] = 0xAAAAAAAAu;                         // an absent worker adds t + 2 = 0
+                    if (w0 + j < W && in_codes)
+                        x[j] = *reinterpret_cast<const uint32_t*>(p.codes[w0 + j] + byte0);
+                }
+                Nib a = {0u, 0u};
+#pragma unroll
+                for (int j = 0; j < 5; ++j) nib_add(a, x[j]);
+                widen_add(acc, a);
             }
-            Nib a = {0u, 0u};
-#pragma unroll
-            for (int j = 0; j < 5; ++j) nib_add(a, x[j]);
-            widen_add(acc, a);
+            // counters hold 128 + k: flip bit 7 to get k as int8
+            acc.e_lo ^= 0x80808080u; acc.o_lo ^= 0x80808080u; acc.e_hi ^= 0x80808080u; acc.o_hi ^= 0x80808080u;
+            gather_bytes(D, acc);
+            if (!in_codes) D[0] = D[1] = D[2] = D[3] = 0u;
+        } else if (SRC == SRC_K8) {
+            const int64_t byte0 = e0 + 16 * lane;
+            uint4 q = make_uint4(0u, 0u, 0u, 0u);
+            if (byte0 < p.ksum_bytes) q = *reinterpret_cast<const uint4*>(p.ksum_in + byte0);
+            D[0] = q.x, D[1] = q.y, D[2] = q.z, D[3] = q.w;
+        } else {
+            const int64_t byte0 = (e0 >> 1) + 8 * lane;
+            uint2 q = make_uint2(0u, 0u);
+            if (byte0 < p.ksum_bytes) q = *reinterpret_cast<const uint2*>(p.ksum_in + byte0);
+            // nibble j of q.x / q.y = element j / 8 + j
+            const uint32_t lo0 = q.x & 0x0F0F0F0Fu, hi0 = (q.x >> 4) & 0x0F0F0F0Fu;
+            const uint32_t lo1 = q.y & 0x0F0F0F0Fu, hi1 = (q.y >> 4) & 0x0F0F0F0Fu;
+            D[0] = sext_nibbles(__builtin_amdgcn_perm(hi0, lo0, 0x05010400u));
+            D[1] = sext_nibbles(__builtin_amdgcn_perm(hi0, lo0, 0x07030602u));
+            D[2] = sext_nibbles(__builtin_amdgcn_perm(hi1, lo1, 0x05010400u));
+            D[3] = sext_nibbles(__builtin_amdgcn_perm(hi1, lo1, 0x07030602u));
         }
-        // counters hold 128 + k: flip bit 7 to get k as int8
-        acc.e_lo ^= 0x80808080u; acc.o_lo ^= 0x80808080u; acc.e_hi ^= 0x80808080u; acc.o_hi ^= 0x80808080u;
-        gather_bytes(D, acc);
-        if (!in_codes) D[0] = D[1] = D[2] = D[3] = 0u;
-    } else if (SRC == SRC_K8) {
-        const int64_t byte0 = e0 + 16 * lane;
-        uint4 q = make_uint4(0u, 0u, 0u, 0u);
-        if (byte0 < p.ksum_bytes) q = *reinterpret_cast<const uint4*>(p.ksum_in + byte0);
-        D[0] = q.x, D[1] = q.y, D[2] = q.z, D[3] = q.w;
-    } else {
-        const int64_t byte0 = (e0 >> 1) + 8 * lane;
-        uint2 q = make_uint2(0u, 0u);
-        if (byte0 < p.ksum_bytes) q = *reinterpret_cast<const uint2*>(p.ksum_in + byte0);
-        // nibble j of q.x / q.y = element j / 8 + j
-        const uint32_t lo0 = q.x & 0x0F0F0F0Fu, hi0 = (q.x >> 4) & 0x0F0F0F0Fu;
-        const uint32_t lo1 = q.y & 0x0F0F0F0Fu, hi1 = (q.y >> 4) & 0x0F0F0F0Fu;
-        D[0] = sext_nibbles(__builtin_amdgcn_perm(hi0, lo0, 0x05010400u));
-        D[1] = sext_nibbles(__builtin_amdgcn_perm(hi0, lo0, 0x07030602u));
-        D[2] = sext_nibbles(__builtin_amdgcn_perm(hi1, lo1, 0x05010400u));
-        D[3] = sext_nibbles(__builtin_amdgcn_perm(hi1, lo1, 0x07030602u));
     }
 
     // ---- sinks that keep k: the lane's 16 fields are already consecutive in memory ----
     if (DST == DST_K8) {
         const int64_t byte0 = e0 + 16 * lane;
-        if (byte0 < p.ksum_bytes) *reinterpret_cast<uint4*>(p.ksum_out + byte0) = make_uint4(D[0], D[1], D[2], D[3]);
+        if (valid && byte0 < p.ksum_bytes)
+            *reinterpret_cast<uint4*>(p.ksum_out + byte0) = make_uint4(D[0], D[1], D[2], D[3]);
         return;
     }
     if (DST == DST_K4) {
         const int64_t byte0 = (e0 >> 1) + 8 * lane;
-        if (byte0 < p.ksum_bytes)
+        if (valid && byte0 < p.ksum_bytes)
             *reinterpret_cast<uint2*>(p.ksum_out + byte0) = make_uint2(pack_nibbles(D[0], D[1]), pack_nibbles(D[2], D[3]));
         return;
     }
 
-    // ---- sinks that scale: transpose the bytes so that every lane stores whole float4s ----
-    uint32_t* row = lds[wave];
-    *reinterpret_cast<uint4*>(row + 4 * lane) = make_uint4(D[0], D[1], D[2], D[3]);
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-    __builtin_amdgcn_wave_barrier();
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    // ---- sinks that scale: the bytes go through LDS (a 64 x 16 -> 256 x 4 transpose per tile) ----
+    *reinterpret_cast<uint4*>(&lds[wave][4 * lane]) = make_uint4(D[0], D[1], D[2], D[3]);
+    __syncthreads();
 
-    const int l0 = layer_from(p.off, p.n_layers, p.tile_layer[e0 >> kTileShift], e0);
-    const bool one_layer = p.off[l0 + 1] >= e0 + kWaveTile || l0 + 1 >= p.n_layers;
-    if (one_layer && full) {
-        const float sc = p.s_shared[l0] / fW;
-        float* dst = p.avg + e0 + 4 * lane;
 #pragma unroll
-        for (int k = 0; k < 4; ++k) {
-            float4 o = scale4(row[64 * k + lane], sc);
-            if (UPDATE) o = apply4(wv[k], o, p.eta);
-            store4<NT>(dst + 256 * k, o);
-        }
-    } else {
-        // layers change inside the tile, or the tile is ragged: the layer of the element at
-        // tile position x is l0 + #{ j > l0 : off[j] - e0 <= x } (one scalar pass over the
-        // boundaries inside the tile); one scale per element
-#pragma unroll
-        for (int k = 0; k < 4; ++k) {
-            const int x0 = 256 * k + 4 * lane;
-            const int64_t e = e0 + x0;
+    for (int t = 0; t < kTilesPerBlock; ++t) {
+        const int64_t tile = tile0 + t;
+        if (tile >= p.n_wave_tiles) break;
+        const int64_t te0 = tile * kWaveTile;
+        const int64_t e = te0 + xq;
+        const uint32_t d = lds[t][64 * wave + lane];
+        const int l0 = layer_from(p.off, p.n_layers, p.tile_layer[te0 >> kTileShift], te0);
+        const bool one_layer = p.off[l0 + 1] >= te0 + kWaveTile || l0 + 1 >= p.n_layers;
+        if (one_layer && te0 + kWaveTile <= p.n) {
+            float4 o = scale4(d, p.s_shared[l0] / fW);
+            if (UPDATE) o = apply4(wv[t], o, p.eta);
+            store4<NT>(p.avg + e, o);
+        } else {
+            // layers change inside the tile, or the tile is ragged: the layer of the element at
+            // tile position x is l0 + #{ j > l0 : off[j] - te0 <= x } (one scalar pass over the
+            // boundaries inside the tile); one scale per element
             int l[4] = {l0, l0, l0, l0};
             for (int j = l0 + 1; j < p.n_layers; ++j) {
-                const int64_t rel = p.off[j] - e0;
+                const int64_t rel = p.off[j] - te0;
                 if (rel >= kWaveTile) break;
                 const int r = (int)rel;
 #pragma unroll
-                for (int i = 0; i < 4; ++i) l[i] += (x0 + i >= r) ? 1 : 0;
+                for (int i = 0; i < 4; ++i) l[i] += (xq + i >= r) ? 1 : 0;
             }
-            const int d = (int)row[64 * k + lane];
-            const int kk[4] = {(int)(int8_t)d, (int)(int8_t)(d >> 8), (int)(int8_t)(d >> 16), d >> 24};
+            const int di = (int)d;
+            const int kk[4] = {(int)(int8_t)di, (int)(int8_t)(di >> 8), (int)(int8_t)(di >> 16), di >> 24};
             float o[4];
 #pragma unroll
             for (int i = 0; i < 4; ++i) {

@@ -123,3 +123,10 @@ def test_vgg_a_full(oracle, binding):
 def test_flat_1e9_full(oracle, binding):
     from paper_1705_07878_amd import workloads
     _full_config(oracle, binding, workloads.flat())
+
+
+def test_indices_beyond_2_31(oracle, binding):
+    """one worker, two layers, n = 2^31 + 70001: element, byte and Philox-block indices past 32 bits"""
+    from paper_1705_07878_amd import workloads
+    wl = workloads.custom([(1 << 31) - 12345, 12345 + 70001], 1, name="beyond 2^31", sigma_fixed=2e-3)
+    _full_config(oracle, binding, wl)

@@ -69,6 +69,9 @@ def lib() -> ctypes.CDLL:
         L.tgo_sum_pack.restype = None
         L.tgo_decode_sum.argtypes = [c_u8, ctypes.c_int, ctypes.c_int, ctypes.c_int64, c_i64, c_f, c_f]
         L.tgo_decode_sum.restype = None
+        L.tgo_unpack_update_momentum.argtypes = [ctypes.POINTER(c_u8), ctypes.c_int, ctypes.c_int64, c_i64, c_f,
+                                                 ctypes.c_float, ctypes.c_float, c_f, c_f]
+        L.tgo_unpack_update_momentum.restype = None
         _lib = L
     return _lib
 
@@ -228,3 +231,22 @@ def decode_sum(ksum, bits: int, n_workers: int, off, s_shared):
     lib().tgo_decode_sum(ksum.ctypes.data_as(ctypes.POINTER(ctypes.c_uint8)), int(bits), int(n_workers), L, op, sp,
                          _f32(avg)[1])
     return avg
+
+
+def unpack_update_momentum(codes_list, off, s_shared, eta, mu, velocity, weights):
+    """-> (new velocity, new weights): v = mu*v + avg ; w = w - eta*v  (inputs not modified)"""
+    off = _check_offsets(off)
+    _, op = _i64(off)
+    L = off.size - 1
+    n = int(off[-1])
+    keep = [np.ascontiguousarray(c, dtype=np.uint8) for c in codes_list]
+    for c in keep:
+        assert c.size >= (n + 3) // 4
+    u8p = ctypes.POINTER(ctypes.c_uint8)
+    arr = (u8p * len(keep))(*[c.ctypes.data_as(u8p) for c in keep])
+    s_shared, sp = _f32(s_shared)
+    v = np.array(velocity, dtype=np.float32, copy=True)
+    w = np.array(weights, dtype=np.float32, copy=True)
+    assert v.size == n and w.size == n and s_shared.size == L
+    lib().tgo_unpack_update_momentum(arr, len(keep), L, op, sp, np.float32(eta), np.float32(mu), _f32(v)[1], _f32(w)[1])
+    return v, w

@@ -217,3 +217,19 @@ void tgo_decode_sum(const uint8_t* ksum, int bits, int n_workers, int64_t n_laye
         avg[e] = (float)((double)k * (double)s_shared[l] / (double)n_workers);
     }
 }
+
+void tgo_unpack_update_momentum(const uint8_t* const* codes, int n_workers, int64_t n_layers,
+                                const int64_t* off, const float* s_shared, float eta, float mu,
+                                float* velocity, float* weights) {
+    const int64_t n = off[n_layers];
+    #pragma omp parallel for num_threads(g_threads) schedule(static)
+    for (int64_t e = 0; e < n; ++e) {
+        const int64_t l = layer_of(e, n_layers, off);
+        long k = 0;
+        for (int w = 0; w < n_workers; ++w) k += tgo_code_at(codes[w], e);
+        const double avg = (double)k * (double)s_shared[l] / (double)n_workers;
+        const double v = (double)mu * (double)velocity[e] + avg;
+        velocity[e] = (float)v;
+        weights[e] = (float)((double)weights[e] - (double)eta * v);
+    }
+}

@@ -100,6 +100,13 @@ void tgo_unpack_update(const uint8_t* const* codes, int n_workers, int64_t n_lay
  * worker order.  grads: W host pointers to n floats; avg: [n]. */
 void tgo_average_float(const float* const* grads, int n_workers, int64_t n, float* avg);
 
+/* The same update with momentum, the optimizer most of the paper's experiments use (Section 4):
+ *   v_e <- (float)( mu * v_e + avg_e ) ;  w_e <- (float)( w_e - eta * v_e(new, unrounded) ),
+ * avg_e = k_e * s_shared_l / W, everything in fp64, each output rounded once. */
+void tgo_unpack_update_momentum(const uint8_t* const* codes, int n_workers, int64_t n_layers,
+                                const int64_t* off, const float* s_shared, float eta, float mu,
+                                float* velocity, float* weights);
+
 /* Server-to-worker pull with parameter localization + scaler sharing (Section 3.1): the
  * averaged gradient has at most 2N+1 levels k * s/N, so the server sends the integer
  * k_e = sum_w t_w(e) in a `bits`-wide two's-complement field (bits = 4 needs 2N+1 <= 16,

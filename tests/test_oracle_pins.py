@@ -458,3 +458,32 @@ def test_sum_pack_fields_and_decode_roundtrip(oracle):
         assert np.array_equal(got, k)
         s = (np.abs(rng.normal(size=len(sizes))) + 0.1).astype(np.float32)
         assert np.array_equal(oracle.decode_sum(packed, bits, W, off, s), oracle.unpack_average(codes, off, s))
+
+
+def test_momentum_update_matches_its_recurrence(oracle):
+    """v <- mu v + avg ; w <- w - eta v: against numpy in fp64; mu = 0 is the plain update; a constant
+    gradient reaches the geometric-series limit v = avg / (1 - mu)"""
+    rng = np.random.default_rng(20)
+    sizes = [33, 100]
+    off = np.concatenate([[0], np.cumsum(sizes)])
+    n, W = int(off[-1]), 4
+    lay = np.repeat(np.arange(2), sizes)
+    s = np.array([0.02, 0.3], np.float32)
+    ts = [rng.integers(-1, 2, size=n) for _ in range(W)]
+    codes = [_forced(oracle, t) for t in ts]
+    avg = np.mean([t * s[lay].astype(np.float64) for t in ts], axis=0)
+    v0 = rng.normal(size=n).astype(np.float32) * 0.1
+    w0 = rng.normal(size=n).astype(np.float32)
+    v1, w1 = oracle.unpack_update_momentum(codes, off, s, 0.05, 0.9, v0, w0)
+    v_want = np.float32(0.9) * v0.astype(np.float64) + avg
+    assert np.allclose(v1, v_want, rtol=2e-7, atol=1e-12)
+    assert np.allclose(w1, w0 - np.float64(np.float32(0.05)) * v_want, rtol=2e-7, atol=1e-12)
+    v2, w2 = oracle.unpack_update_momentum(codes, off, s, 0.05, 0.0, v0, w0)
+    assert np.array_equal(w2, oracle.unpack_update(codes, off, s, 0.05, w0))
+    assert np.array_equal(v2, oracle.unpack_average(codes, off, s))
+    v = np.zeros(n, np.float32)
+    w = w0
+    for _ in range(400):
+        v, w = oracle.unpack_update_momentum(codes, off, s, 0.0, 0.9, v, w)
+    assert np.allclose(v, avg / (1 - np.float64(np.float32(0.9))), rtol=1e-5, atol=1e-9)
+    assert np.array_equal(w, w0)

@@ -149,7 +149,19 @@ def main():
     upd_gbs = n * (8.0 + 0.25 * W) / (upd_ms * 1e-3) / 1e9
     kern["unpack_update (not in step)"] = {"ms": round(upd_ms, 4), "algorithmic_GBps": round(upd_gbs, 1),
                                            "pct_hbm_peak": round(100 * upd_gbs / HBM_PEAK_GBS, 1)}
-    del weights
+    velocity = torch.zeros((n,), dtype=torch.float32, device="cuda")
+    for _ in range(2):
+        plan.tg_unpack_update_momentum(codes, s_shared, 1e-3, 0.9, velocity, weights)
+    e0.record(stream)
+    for _ in range(reps):
+        plan.tg_unpack_update_momentum(codes, s_shared, 1e-3, 0.9, velocity, weights)
+    e1.record(stream)
+    torch.cuda.synchronize()
+    mom_ms = e0.elapsed_time(e1) / reps
+    mom_gbs = n * (16.0 + 0.25 * W) / (mom_ms * 1e-3) / 1e9
+    kern["unpack_update_momentum (not in step)"] = {"ms": round(mom_ms, 4), "algorithmic_GBps": round(mom_gbs, 1),
+                                                    "pct_hbm_peak": round(100 * mom_gbs / HBM_PEAK_GBS, 1)}
+    del weights, velocity
 
     # Section 3.1 server-to-worker pull (not part of the timed step): the average as k in narrow fields
     bits = 4 if W <= 7 else 8

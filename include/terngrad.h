@@ -156,6 +156,14 @@ tg_status tg_unpack_average(tg_plan* plan, int n_workers, const uint8_t* const* 
 tg_status tg_unpack_update(tg_plan* plan, int n_workers, const uint8_t* const* codes,
                            const float* s_shared, float eta, float* weights, void* stream);
 
+/* The same with momentum (the optimizer of most experiments in Section 4):
+ *   velocity[e] <- mu * velocity[e] + avg[e] ;  weights[e] <- weights[e] - eta * velocity[e]
+ * (two fused multiply-adds; mu = 0 reproduces tg_unpack_update and leaves avg in velocity).
+ *   velocity, weights  dev [n] fp32, in/out, 16-byte aligned, distinct buffers; eta, mu finite */
+tg_status tg_unpack_update_momentum(tg_plan* plan, int n_workers, const uint8_t* const* codes,
+                                    const float* s_shared, float eta, float mu, float* velocity,
+                                    float* weights, void* stream);
+
 /* Server-to-worker pull (Section 3.1): with parameter localization and a shared scaler the
  * averaged gradient has at most 2N+1 levels k * s/N, so it can travel as the integer
  * k = sum_w t_w in a narrow field instead of a 32-bit float (the paper's 32 / log2(1+2N)).

@@ -61,6 +61,8 @@ lib.tg_unpack_average.argtypes = [_vp, ctypes.c_int, _pp, _vp, _vp, _vp]
 lib.tg_unpack_average.restype = ctypes.c_int
 lib.tg_unpack_update.argtypes = [_vp, ctypes.c_int, _pp, _vp, ctypes.c_float, _vp, _vp]
 lib.tg_unpack_update.restype = ctypes.c_int
+lib.tg_unpack_update_momentum.argtypes = [_vp, ctypes.c_int, _pp, _vp, ctypes.c_float, ctypes.c_float, _vp, _vp, _vp]
+lib.tg_unpack_update_momentum.restype = ctypes.c_int
 lib.tg_sum_bytes.argtypes = [_vp, ctypes.c_int]
 lib.tg_sum_bytes.restype = _i64
 lib.tg_unpack_sum_pack.argtypes = [_vp, ctypes.c_int, _pp, ctypes.c_int, _vp, _vp]
@@ -215,3 +217,10 @@ class Plan:
     def tg_decode_sum(self, n_workers: int, ksum, bits: int, s_shared, avg, stream=None):
         _check(lib.tg_decode_sum(self._h, int(n_workers), _ptr(ksum), int(bits), _ptr(s_shared), _ptr(avg),
                                  _stream(stream)), "tg_decode_sum")
+
+    def tg_unpack_update_momentum(self, codes: Sequence, s_shared, eta: float, mu: float, velocity, weights,
+                                  stream=None):
+        cp, _k = _ptr_array(codes)
+        _check(lib.tg_unpack_update_momentum(self._h, len(codes), cp, _ptr(s_shared), float(eta), float(mu),
+                                             _ptr(velocity), _ptr(weights), _stream(stream)),
+               "tg_unpack_update_momentum")

@@ -357,6 +357,25 @@ tg_status tg_unpack_update(tg_plan* p, int n_workers, const uint8_t* const* code
     return launch_unpack<tg::SRC_CODES, tg::DST_UPDATE>(p, a, stream);
 }
 
+tg_status tg_unpack_update_momentum(tg_plan* p, int n_workers, const uint8_t* const* codes,
+                                    const float* s_shared, float eta, float mu, float* velocity,
+                                    float* weights, void* stream) {
+    tg_status st = check_workers(p, n_workers);
+    if (st != TG_OK) return st;
+    if (codes == nullptr || s_shared == nullptr || weights == nullptr || velocity == nullptr ||
+        !std::isfinite(eta) || !std::isfinite(mu) || velocity == weights)
+        return TG_ERR_INVALID_ARG;
+    tg::UnpackArgs a{};
+    if ((st = fill_unpack(p, n_workers, codes, a)) != TG_OK) return st;
+    if (!aligned(s_shared, 4) || !aligned(weights, 16) || !aligned(velocity, 16)) return TG_ERR_ALIGNMENT;
+    a.s_shared = s_shared;
+    a.avg = weights;
+    a.velocity = velocity;
+    a.eta = eta;
+    a.mu = mu;
+    return launch_unpack<tg::SRC_CODES, tg::DST_MOMENTUM>(p, a, stream);
+}
+
 int64_t tg_sum_bytes(const tg_plan* p, int bits) {
     if (p == nullptr || (bits != 4 && bits != 8)) return -1;
     return sum_bytes(p, bits);

@@ -25,6 +25,8 @@ struct UnpackArgs {
     const int32_t* tile_layer;
     float* avg;                 // [n]: the average (out), or the weights (in/out) when updating
     float eta;                  // learning rate of the fused update
+    float mu;                   // momentum of the fused update
+    float* velocity;            // [n] momentum buffer (in/out), DST_MOMENTUM only
     const uint8_t* ksum_in;     // packed sums k (4- or 8-bit fields), when they are the source
     uint8_t* ksum_out;          // packed sums k, when they are the sink
     int64_t ksum_bytes;         // size of that buffer: ceil(n * bits / 8) rounded up to 16
@@ -104,10 +106,12 @@ __device__ __forceinline__ float4 apply4(const float4 w, const float4 a, const f
 //   sink    DST_AVG:    avg[e] = k * (s/W)               (Algorithm 1, server line)
 //           DST_UPDATE: w[e]  -= eta * k * (s/W)          (server line fused with the update line:
 //                       the average is never written to or re-read from HBM)
+//           DST_MOMENTUM: v[e] = mu * v[e] + k * (s/W) ; w[e] -= eta * v[e]   (momentum SGD,
+//                       the optimizer of most of the paper's experiments)
 //           DST_K4 / DST_K8: k itself in 4- / 8-bit fields (the server-to-worker pull of
 //                       Section 3.1: at most 2N+1 levels instead of 32-bit floats)
 enum { SRC_CODES = 0, SRC_K4 = 1, SRC_K8 = 2 };
-enum { DST_AVG = 0, DST_UPDATE = 1, DST_K4 = 2, DST_K8 = 3 };
+enum { DST_AVG = 0, DST_UPDATE = 1, DST_K4 = 2, DST_K8 = 3, DST_MOMENTUM = 4 };
 
 // sign-extend the low nibble of every byte: bit 3 set -> bits 4..7 set (0x08 * 30 = 0xF0)
 __device__ __forceinline__ uint32_t sext_nibbles(const uint32_t y) {
@@ -131,7 +135,8 @@ __global__ void __launch_bounds__(kBlock) unpack_average_kernel(const UnpackArgs
     const int wave = wave_uniform(threadIdx.x >> 6);
     const int W = p.n_workers;
     const float fW = (float)W;
-    constexpr bool UPDATE = DST == DST_UPDATE;
+    constexpr bool MOMENTUM = DST == DST_MOMENTUM;
+    constexpr bool UPDATE = DST == DST_UPDATE || MOMENTUM;
 
     // A workgroup owns 4 consecutive tiles.  Wave j sums the codes of tile j (one short-lived pass,
     // every table lookup a scalar load); after a barrier the four waves write each tile together,
@@ -143,13 +148,16 @@ __global__ void __launch_bounds__(kBlock) unpack_average_kernel(const UnpackArgs
     const int64_t e0 = wt * kWaveTile;
     const int xq = 256 * wave + 4 * lane;              // this lane's position inside any tile when storing
 
-    float4 wv[kTilesPerBlock];
+    float4 wv[kTilesPerBlock], vv[MOMENTUM ? kTilesPerBlock : 1];
     if (UPDATE) {
-        // the weights depend on nothing: issue their loads first
+        // the weights (and velocities) depend on nothing: issue their loads first
 #pragma unroll
         for (int t = 0; t < kTilesPerBlock; ++t) {
             const int64_t e = (tile0 + t) * kWaveTile + xq;
-            if (e + 3 < p.n) wv[t] = load_stream(p.avg + e);
+            if (e + 3 < p.n) {
+                wv[t] = load_stream(p.avg + e);
+                if (MOMENTUM) vv[t] = load_stream(p.velocity + e);
+            }
         }
     }
 
@@ -227,6 +235,12 @@ __global__ void __launch_bounds__(kBlock) unpack_average_kernel(const UnpackArgs
         const bool one_layer = p.off[l0 + 1] >= te0 + kWaveTile || l0 + 1 >= p.n_layers;
         if (one_layer && te0 + kWaveTile <= p.n) {
             float4 o = scale4(d, p.s_shared[l0] / fW);
+            if (MOMENTUM) {
+                const float4 v = vv[t];
+                o = make_float4(__builtin_fmaf(p.mu, v.x, o.x), __builtin_fmaf(p.mu, v.y, o.y),
+                                __builtin_fmaf(p.mu, v.z, o.z), __builtin_fmaf(p.mu, v.w, o.w));
+                store4<NT>(p.velocity + e, o);
+            }
             if (UPDATE) o = apply4(wv[t], o, p.eta);
             store4<NT>(p.avg + e, o);
         } else {
@@ -247,6 +261,10 @@ __global__ void __launch_bounds__(kBlock) unpack_average_kernel(const UnpackArgs
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
                 o[i] = (float)kk[i] * (p.s_shared[l[i]] / fW);
+                if (MOMENTUM && e + i < p.n) {
+                    o[i] = __builtin_fmaf(p.mu, p.velocity[e + i], o[i]);
+                    p.velocity[e + i] = o[i];
+                }
                 if (UPDATE && e + i < p.n) o[i] = __builtin_fmaf(-p.eta, o[i], p.avg[e + i]);
             }
             if (e + 3 < p.n) {

@@ -192,6 +192,45 @@ def test_sum_pack_rejects_fields_that_cannot_hold_the_sum(binding):
         plan.close()
 
 
+def test_momentum_update(oracle, binding):
+    rng = np.random.default_rng(23)
+    off = _off([5000, 3, 4096, 2001, 20000])
+    n = int(off[-1])
+    for W, eta, mu in ((1, 0.1, 0.9), (4, 0.01, 0.9), (8, 0.5, 0.0), (5, 0.0, 0.5)):
+        grads = _grads(rng, off, W)
+        st = [oracle.clip_stats(g, off, 2.5) for g in grads]
+        s = oracle.share_scalers(np.stack([x[1] for x in st]))
+        codes = [oracle.ternarize_pack(g, off, st[w][0], s, 9, 1, w) for w, g in enumerate(grads)]
+        v0 = (rng.normal(size=n) * float(s.max())).astype(np.float32)
+        w0 = rng.normal(size=n).astype(np.float32)
+        plan = binding.Plan(off, W)
+        try:
+            cd = []
+            for c in codes:
+                buf = np.zeros(plan.packed_bytes, np.uint8)
+                buf[:c.size] = c
+                cd.append(dev(buf))
+            v, w = dev(v0), dev(w0)
+            plan.tg_unpack_update_momentum(cd, dev(s), eta, mu, v, w)
+            torch.cuda.synchronize()
+            v_want, w_want = oracle.unpack_update_momentum(codes, off, s, eta, mu, v0, w0)
+            avg = oracle.unpack_average(codes, off, s)
+            vg, wg = v.cpu().numpy(), w.cpu().numpy()
+            # v' = mu v + avg: within 1e-6 of the larger term; w' = w - eta v': likewise
+            v64 = v_want.astype(np.float64)
+            sc_v = np.maximum(np.abs(mu * v0.astype(np.float64)), np.abs(avg.astype(np.float64)))
+            assert np.all(np.abs(vg - v64) <= 1e-6 * sc_v + 1e-45)
+            sc_w = np.maximum(np.abs(w0.astype(np.float64)), np.abs(eta * v64))
+            assert np.all(np.abs(wg - w_want.astype(np.float64)) <= 1e-6 * sc_w)
+            if mu == 0.0:
+                assert np.array_equal(vg, gpu_unpack_average(plan, codes, s))
+                assert np.array_equal(wg, gpu_unpack_update(plan, codes, s, eta, w0))
+            with pytest.raises(binding.TgError):
+                plan.tg_unpack_update_momentum(cd, dev(s), eta, mu, w, w)
+        finally:
+            plan.close()
+
+
 def test_extreme_scalers(oracle, binding):
     """tiny (subnormal threshold products), huge and zero scalers: same decisions on both sides"""
     rng = np.random.default_rng(10)

@@ -35,6 +35,8 @@ struct Tables {
     std::vector<int32_t> seg_layer;
     std::vector<int64_t> seg_begin, seg_end, seg_pivot;
     std::vector<int64_t> layer_seg;   // [L+1]
+    std::vector<int64_t> unit_first;  // workgroups of the statistics pass
+    std::vector<int32_t> unit_count;
 };
 
 tg_status check_offsets(int64_t n_layers, const int64_t* off) {
@@ -79,6 +81,22 @@ void build_tables(int64_t L, const int64_t* off, Tables& T) {
         }
     }
     while (next_layer_mark <= L) T.layer_seg[(size_t)next_layer_mark++] = (int64_t)T.seg_layer.size();
+    // workgroups: one large segment each, or up to four consecutive small ones (a wave each)
+    const int64_t n_segs = (int64_t)T.seg_layer.size();
+    for (int64_t i = 0; i < n_segs;) {
+        auto small = [&](int64_t k) { return T.seg_end[(size_t)k] - T.seg_begin[(size_t)k] <= tg::kSmallSeg; };
+        if (!small(i)) {
+            T.unit_first.push_back(i);
+            T.unit_count.push_back(0);
+            ++i;
+        } else {
+            int32_t cnt = 1;
+            while (cnt < tg::kBlock / tg::kWave && i + cnt < n_segs && small(i + cnt)) ++cnt;
+            T.unit_first.push_back(i);
+            T.unit_count.push_back(cnt);
+            i += cnt;
+        }
+    }
 }
 
 template <class T>
@@ -94,13 +112,15 @@ bool aligned(const void* p, uintptr_t a) { return ((uintptr_t)p & (a - 1)) == 0;
 }  // namespace
 
 struct tg_plan {
-    int64_t n_layers = 0, n = 0, packed_bytes = 0, n_tiles = 0, n_segs = 0;
+    int64_t n_layers = 0, n = 0, packed_bytes = 0, n_tiles = 0, n_segs = 0, n_units = 0;
     int max_workers = 0;
     int64_t* d_off = nullptr;
     int32_t* d_tile_layer = nullptr;
     int64_t* d_seg_begin = nullptr;
     int64_t* d_seg_end = nullptr;
     int64_t* d_seg_pivot = nullptr;
+    int64_t* d_unit_first = nullptr;
+    int32_t* d_unit_count = nullptr;
     int64_t* d_layer_seg = nullptr;
     double* d_psum = nullptr;
     double* d_psq = nullptr;
@@ -201,13 +221,15 @@ tg_status tg_plan_create(int64_t n_layers, const int64_t* offsets, int max_worke
     p->packed_bytes = (((T.n + 3) / 4) + 15) / 16 * 16;
     p->n_tiles = T.n_tiles;
     p->n_segs = (int64_t)T.seg_layer.size();
+    p->n_units = (int64_t)T.unit_first.size();
     p->max_workers = max_workers;
 
     const std::vector<int64_t> off(offsets, offsets + n_layers + 1);
     const size_t np = (size_t)p->n_segs * (size_t)max_workers;
     bool ok = upload(&p->d_off, off) && upload(&p->d_tile_layer, T.tile_layer) &&
               upload(&p->d_seg_begin, T.seg_begin) && upload(&p->d_seg_end, T.seg_end) &&
-              upload(&p->d_seg_pivot, T.seg_pivot) &&
+              upload(&p->d_seg_pivot, T.seg_pivot) && upload(&p->d_unit_first, T.unit_first) &&
+              upload(&p->d_unit_count, T.unit_count) &&
               upload(&p->d_layer_seg, T.layer_seg) &&
               hip_ok(hipMalloc((void**)&p->d_psum, np * sizeof(double))) &&
               hip_ok(hipMalloc((void**)&p->d_psq, np * sizeof(double))) &&
@@ -223,7 +245,7 @@ tg_status tg_plan_create(int64_t n_layers, const int64_t* offsets, int max_worke
 
 tg_status tg_plan_destroy(tg_plan* p) {
     if (p == nullptr) return TG_OK;
-    void* bufs[] = {p->d_off, p->d_tile_layer, p->d_seg_begin, p->d_seg_end, p->d_seg_pivot,
+    void* bufs[] = {p->d_off, p->d_tile_layer, p->d_seg_begin, p->d_seg_end, p->d_seg_pivot, p->d_unit_first, p->d_unit_count,
                     p->d_layer_seg, p->d_psum, p->d_psq, p->d_pmax};
     bool ok = true;
     for (void* b : bufs)
@@ -254,6 +276,8 @@ tg_status tg_clip_stats(tg_plan* p, int n_workers, const float* const* grads, fl
         a.grads[w] = grads[w];
     }
     if (!aligned(tau, 4) || !aligned(s_local, 4)) return TG_ERR_ALIGNMENT;
+    a.unit_first = p->d_unit_first;
+    a.unit_count = p->d_unit_count;
     a.seg_begin = p->d_seg_begin;
     a.seg_end = p->d_seg_end;
     a.seg_pivot = p->d_seg_pivot;
@@ -262,7 +286,7 @@ tg_status tg_clip_stats(tg_plan* p, int n_workers, const float* const* grads, fl
     a.pmax = p->d_pmax;
     a.n_segs = p->n_segs;
     hipStream_t s = (hipStream_t)stream;
-    hipLaunchKernelGGL(tg::clip_stats_partial_kernel, dim3((unsigned)p->n_segs, (unsigned)n_workers),
+    hipLaunchKernelGGL(tg::clip_stats_partial_kernel, dim3((unsigned)p->n_units, (unsigned)n_workers),
                        dim3(tg::kBlock), 0, s, a);
     if (!hip_ok(hipGetLastError())) return TG_ERR_HIP;
 
@@ -278,8 +302,9 @@ tg_status tg_clip_stats(tg_plan* p, int n_workers, const float* const* grads, fl
     f.n_layers = (int32_t)p->n_layers;
     f.c = c;
     f.noclip = (!(c > 0.0f) || std::isinf(c)) ? 1 : 0;
-    hipLaunchKernelGGL(tg::clip_stats_final_kernel, dim3((unsigned)p->n_layers, (unsigned)n_workers),
-                       dim3(tg::kFinalBlock), 0, s, f);
+    const int64_t fblocks = (p->n_layers + tg::kBlock / tg::kWave - 1) / (tg::kBlock / tg::kWave);
+    hipLaunchKernelGGL(tg::clip_stats_final_kernel, dim3((unsigned)fblocks, (unsigned)n_workers),
+                       dim3(tg::kBlock), 0, s, f);
     if (!hip_ok(hipGetLastError())) return TG_ERR_HIP;
     return TG_OK;
 }

@@ -4,9 +4,10 @@
 // same pass.  Sums are fp64 and taken about a per-layer pivot K = first element
 // of the layer (shifted-data variance: exact for a constant layer, insensitive to
 // a large mean).  No float atomics: every statistics chunk (16384 elements, 65536 for
-// gradients beyond 2^27 elements) is cut into segments, one per layer it touches; one
-// workgroup reduces one segment in a fixed tree and writes one partial; a second small
-// kernel folds the partials of each layer in a fixed order.  Results are bit-identical from
+// gradients beyond 2^27 elements) is cut into segments, one per layer it touches; a
+// workgroup reduces one large segment (or four small ones, a wave each) in a fixed tree and
+// writes one partial per segment; a second small kernel folds the partials of each layer in
+// a fixed order.  Results are bit-identical from
 // run to run.
 #pragma once
 
@@ -18,8 +19,12 @@ constexpr int kStatChunk = 16384;       // elements per workgroup: 256 threads x
 constexpr int kStatChunkLarge = 65536;  // for very large gradients (fewer partials to fold)
 constexpr int64_t kStatLargeFrom = (int64_t)1 << 27;
 
+constexpr int kSmallSeg = 2048;         // segments up to this size are reduced by one wave, four per workgroup
+
 struct StatsArgs {
     const float* grads[kMaxWorkers];
+    const int64_t* unit_first;      // [n_units] first segment of the workgroup's unit
+    const int32_t* unit_count;      // [n_units] 0: one large segment, block-wide; 1..4: that many small segments, one per wave
     const int64_t* seg_begin;       // [n_segs]
     const int64_t* seg_end;         // [n_segs]
     const int64_t* seg_pivot;       // [n_segs] index of the first element of the segment's layer
@@ -59,17 +64,9 @@ __device__ __forceinline__ Acc wave_reduce(Acc a) {
     return a;
 }
 
-// one workgroup per segment (a run of at most one chunk inside one layer)
-__global__ void __launch_bounds__(kBlock) clip_stats_partial_kernel(const StatsArgs p) {
-    __shared__ double sh1[kBlock / kWave], sh2[kBlock / kWave];
-    __shared__ float shm[kBlock / kWave];
-
-    const int w = blockIdx.y;
-    const float* __restrict__ g = p.grads[w];
-    const int t = threadIdx.x;
-    const int64_t sg = blockIdx.x;
-    const int64_t b = p.seg_begin[sg], e = p.seg_end[sg];
-    const double K = (double)g[p.seg_pivot[sg]];
+// sums of one segment [b, e) over `nthr` cooperating threads (this thread is number t of them)
+__device__ __forceinline__ Acc segment_sums(const float* __restrict__ g, const int64_t b, const int64_t e,
+                                            const double K, const int t, const int nthr) {
     Acc a = {0.0, 0.0, 0.0f};
     const int64_t b4 = (b + 3) & ~(int64_t)3;
     const int64_t e4 = e & ~(int64_t)3;
@@ -78,21 +75,56 @@ __global__ void __launch_bounds__(kBlock) clip_stats_partial_kernel(const StatsA
         const int64_t nv = (e4 - b4) >> 2;          // float4 groups
         int64_t i = t;
         // four streaming loads in flight per thread
-        for (; i + 3 * kBlock < nv; i += 4 * kBlock) {
-            const float4 v0 = load_stream(gp + 4 * i), v1 = load_stream(gp + 4 * (i + kBlock));
-            const float4 v2 = load_stream(gp + 4 * (i + 2 * kBlock)), v3 = load_stream(gp + 4 * (i + 3 * kBlock));
+        for (; i + 3 * nthr < nv; i += 4 * nthr) {
+            const float4 v0 = load_stream(gp + 4 * i), v1 = load_stream(gp + 4 * (i + nthr));
+            const float4 v2 = load_stream(gp + 4 * (i + 2 * nthr)), v3 = load_stream(gp + 4 * (i + 3 * nthr));
             acc_add4(a, v0, K);
             acc_add4(a, v1, K);
             acc_add4(a, v2, K);
             acc_add4(a, v3, K);
         }
-        for (; i < nv; i += kBlock) acc_add4(a, load_stream(gp + 4 * i), K);
+        for (; i < nv; i += nthr) acc_add4(a, load_stream(gp + 4 * i), K);
         // ragged head and tail, at most 3 elements each
         if (t < b4 - b) acc_add(a, g[b + t], K);
         if (t < e - e4) acc_add(a, g[e4 + t], K);
     } else {
-        for (int64_t i = b + t; i < e; i += kBlock) acc_add(a, g[i], K);
+        for (int64_t i = b + t; i < e; i += nthr) acc_add(a, g[i], K);
     }
+    return a;
+}
+
+// One workgroup per unit: either one large segment (a run of at most one chunk inside one layer),
+// reduced by all 256 threads, or up to four small segments, one per wave.
+__global__ void __launch_bounds__(kBlock) clip_stats_partial_kernel(const StatsArgs p) {
+    __shared__ double sh1[kBlock / kWave], sh2[kBlock / kWave];
+    __shared__ float shm[kBlock / kWave];
+
+    const int w = blockIdx.y;
+    const float* __restrict__ g = p.grads[w];
+    const int t = threadIdx.x;
+    const int64_t first = p.unit_first[blockIdx.x];
+    const int count = p.unit_count[blockIdx.x];
+
+    if (count > 0) {
+        // small segments: wave j takes segment first + j
+        const int wave = wave_uniform(t >> 6);
+        if (wave >= count) return;
+        const int64_t sg = first + wave;
+        const double K = (double)g[p.seg_pivot[sg]];
+        Acc a = segment_sums(g, p.seg_begin[sg], p.seg_end[sg], K, t & 63, kWave);
+        a = wave_reduce(a);
+        if ((t & 63) == 0) {
+            const int64_t o = (int64_t)w * p.n_segs + sg;
+            p.psum[o] = a.s1;
+            p.psq[o] = a.s2;
+            p.pmax[o] = a.m;
+        }
+        return;
+    }
+
+    const int64_t sg = first;
+    const double K = (double)g[p.seg_pivot[sg]];
+    Acc a = segment_sums(g, p.seg_begin[sg], p.seg_end[sg], K, t, kBlock);
     a = wave_reduce(a);
     if ((t & 63) == 0) {
         sh1[t >> 6] = a.s1;
@@ -130,48 +162,83 @@ struct StatsFinalArgs {
     int32_t noclip;
 };
 
-constexpr int kFinalBlock = 1024;
+constexpr int kFinalSmall = 64;   // layers with at most this many partials are folded by one wave
 
-__global__ void __launch_bounds__(kFinalBlock) clip_stats_final_kernel(const StatsFinalArgs p) {
-    __shared__ double sh1[kFinalBlock / kWave], sh2[kFinalBlock / kWave];
-    __shared__ float shm[kFinalBlock / kWave];
+__device__ __forceinline__ void finish_layer(const StatsFinalArgs& p, const int l, const int w,
+                                             const double s1, const double s2, const float m) {
+    const int64_t cnt = p.off[l + 1] - p.off[l];
+    double sigma = 0.0;
+    if (cnt > 0) {
+        const double md = s1 / (double)cnt;                     // mean - K
+        const double var = s2 / (double)cnt - md * md;
+        sigma = var > 0.0 ? sqrt(var) : 0.0;
+    }
+    const float tau = p.noclip ? __builtin_inff() : (float)((double)p.c * sigma);
+    const int64_t o = (int64_t)w * p.n_layers + l;
+    p.tau[o] = tau;
+    p.s_local[o] = fminf(m, tau);                               // Eq. 2 on the clipped layer
+}
 
-    const int l = blockIdx.x, w = blockIdx.y, t = threadIdx.x;
-    const int64_t sb = p.layer_seg[l], se = p.layer_seg[l + 1];
+// A workgroup folds the partials of four consecutive layers: one wave per layer when all four are
+// small, else the whole workgroup layer after layer.  Fixed order either way.
+__global__ void __launch_bounds__(kBlock) clip_stats_final_kernel(const StatsFinalArgs p) {
+    __shared__ double sh1[kBlock / kWave], sh2[kBlock / kWave];
+    __shared__ float shm[kBlock / kWave];
+
+    const int w = blockIdx.y, t = threadIdx.x, lane = t & 63;
+    const int wave = wave_uniform(t >> 6);
+    const int l_first = blockIdx.x * (kBlock / kWave);
     const int64_t base = (int64_t)w * p.n_segs;
-    Acc a = {0.0, 0.0, 0.0f};
-    for (int64_t i = sb + t; i < se; i += kFinalBlock) {
-        a.s1 += p.psum[base + i];
-        a.s2 += p.psq[base + i];
-        a.m = fmaxf(a.m, p.pmax[base + i]);
+    const int lw = l_first + wave;
+    int64_t sb = 0, se = 0;
+    if (lw < p.n_layers) {
+        sb = p.layer_seg[lw];
+        se = p.layer_seg[lw + 1];
     }
-    a = wave_reduce(a);
-    if ((t & 63) == 0) {
-        sh1[t >> 6] = a.s1;
-        sh2[t >> 6] = a.s2;
-        shm[t >> 6] = a.m;
+    const int any_large = __syncthreads_or(se - sb > kFinalSmall);
+
+    if (!any_large) {
+        if (lw >= p.n_layers) return;
+        Acc a = {0.0, 0.0, 0.0f};
+        if (sb + lane < se) {
+            a.s1 = p.psum[base + sb + lane];
+            a.s2 = p.psq[base + sb + lane];
+            a.m = p.pmax[base + sb + lane];
+        }
+        a = wave_reduce(a);
+        if (lane == 0) finish_layer(p, lw, w, a.s1, a.s2, a.m);
+        return;
     }
-    __syncthreads();
-    if (t == 0) {
-        double s1 = sh1[0], s2 = sh2[0];
-        float m = shm[0];
+
+    for (int j = 0; j < kBlock / kWave; ++j) {
+        const int l = l_first + j;
+        if (l >= p.n_layers) break;
+        const int64_t b = p.layer_seg[l], e = p.layer_seg[l + 1];
+        Acc a = {0.0, 0.0, 0.0f};
+        for (int64_t i = b + t; i < e; i += kBlock) {
+            a.s1 += p.psum[base + i];
+            a.s2 += p.psq[base + i];
+            a.m = fmaxf(a.m, p.pmax[base + i]);
+        }
+        a = wave_reduce(a);
+        if (lane == 0) {
+            sh1[wave] = a.s1;
+            sh2[wave] = a.s2;
+            shm[wave] = a.m;
+        }
+        __syncthreads();
+        if (t == 0) {
+            double s1 = sh1[0], s2 = sh2[0];
+            float m = shm[0];
 #pragma unroll
-        for (int k = 1; k < kFinalBlock / kWave; ++k) {
-            s1 += sh1[k];
-            s2 += sh2[k];
-            m = fmaxf(m, shm[k]);
+            for (int k = 1; k < kBlock / kWave; ++k) {
+                s1 += sh1[k];
+                s2 += sh2[k];
+                m = fmaxf(m, shm[k]);
+            }
+            finish_layer(p, l, w, s1, s2, m);
         }
-        const int64_t cnt = p.off[l + 1] - p.off[l];
-        double sigma = 0.0;
-        if (cnt > 0) {
-            const double md = s1 / (double)cnt;                     // mean - K
-            const double var = s2 / (double)cnt - md * md;
-            sigma = var > 0.0 ? sqrt(var) : 0.0;
-        }
-        const float tau = p.noclip ? __builtin_inff() : (float)((double)p.c * sigma);
-        const int64_t o = (int64_t)w * p.n_layers + l;
-        p.tau[o] = tau;
-        p.s_local[o] = fminf(m, tau);                               // Eq. 2 on the clipped layer
+        __syncthreads();
     }
 }
 

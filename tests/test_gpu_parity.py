@@ -47,6 +47,15 @@ def test_all_four_calls_small(oracle, binding, sizes, W):
     full_parity(oracle, binding, off, _grads(rng, off, W), c=2.5, seed=1234567, step=3)
 
 
+def test_finer_buckets_than_a_layer(oracle, binding):
+    """Section 3.3: gradients split into buckets that are ternarized independently (as in QSGD): a finer
+    offset table through the same kernels; many boundaries per tile, small statistics segments"""
+    rng = np.random.default_rng(33)
+    for sizes in ([512] * 64 + [256] * 8 + [64] * 16 + [16] * 9, [1024] * 33, [2048, 2049, 2047] * 5, [100] * 333):
+        off = _off(sizes)
+        full_parity(oracle, binding, off, _grads(rng, off, 2), seed=77, step=5)
+
+
 def test_w64_and_worker_base(oracle, binding):
     rng = np.random.default_rng(64)
     off = _off([3000, 17, 5000])

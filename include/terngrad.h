@@ -68,6 +68,9 @@ typedef enum {
 
 /* The paper trains with up to N = 64 workers (Section 4.1, LeNet). */
 #define TG_MAX_WORKERS 64
+/* Largest model a plan accepts: 2^35 elements (128 GiB of fp32 per worker), 2^22 layers. */
+#define TG_MAX_ELEMENTS ((int64_t)1 << 35)
+#define TG_MAX_LAYERS ((int64_t)1 << 22)
 
 /* ---- plan: the offset table of one model, uploaded once ------------------- */
 
@@ -75,7 +78,8 @@ typedef enum {
  * are offsets[0..n_layers] (host), uploads them to the current device and
  * reserves the reduction workspace of tg_clip_stats for up to `max_workers`
  * workers per call.  Requires n_layers >= 1, offsets[0] = 0, offsets
- * non-decreasing, offsets[n_layers] >= 1, 1 <= max_workers <= TG_MAX_WORKERS.
+ * non-decreasing, 1 <= offsets[n_layers] <= TG_MAX_ELEMENTS, n_layers <= TG_MAX_LAYERS,
+ * 1 <= max_workers <= TG_MAX_WORKERS.
  * Errors: TG_ERR_INVALID_ARG, TG_ERR_TOO_MANY_WORKERS, TG_ERR_ALLOC, TG_ERR_HIP. */
 tg_status tg_plan_create(int64_t n_layers, const int64_t* offsets, int max_workers, tg_plan** out);
 

@@ -40,11 +40,12 @@ struct Tables {
 };
 
 tg_status check_offsets(int64_t n_layers, const int64_t* off) {
-    if (n_layers < 1 || n_layers > (int64_t)1 << 24 || off == nullptr) return TG_ERR_INVALID_ARG;
+    // limits keep every launch below 2^32 threads per grid dimension
+    if (n_layers < 1 || n_layers > TG_MAX_LAYERS || off == nullptr) return TG_ERR_INVALID_ARG;
     if (off[0] != 0) return TG_ERR_INVALID_ARG;
     for (int64_t l = 0; l < n_layers; ++l)
         if (off[l + 1] < off[l]) return TG_ERR_INVALID_ARG;
-    if (off[n_layers] < 1 || off[n_layers] > ((int64_t)1 << 40)) return TG_ERR_INVALID_ARG;
+    if (off[n_layers] < 1 || off[n_layers] > TG_MAX_ELEMENTS) return TG_ERR_INVALID_ARG;
     return TG_OK;
 }
 
@@ -130,11 +131,10 @@ struct tg_plan {
 static int64_t sum_bytes(const tg_plan* p, int bits) { return ((p->n * bits + 7) / 8 + 15) / 16 * 16; }
 
 template <int SRC, int DST>
-static tg_status launch_unpack(const tg_plan* p, const tg::UnpackArgs& a, void* stream) {
+static tg_status launch_unpack(const tg::UnpackArgs& a, void* stream) {
     const int64_t blocks = (a.n_wave_tiles + tg::kBlock / tg::kWave - 1) / (tg::kBlock / tg::kWave);
     hipLaunchKernelGGL((tg::unpack_average_kernel<true, SRC, DST>), dim3((unsigned)blocks), dim3(tg::kBlock), 0,
                        (hipStream_t)stream, a);
-    (void)p;
     if (!hip_ok(hipGetLastError())) return TG_ERR_HIP;
     return TG_OK;
 }
@@ -364,7 +364,7 @@ tg_status tg_unpack_average(tg_plan* p, int n_workers, const uint8_t* const* cod
     if (!aligned(s_shared, 4) || !aligned(avg, 16)) return TG_ERR_ALIGNMENT;
     a.s_shared = s_shared;
     a.avg = avg;
-    return launch_unpack<tg::SRC_CODES, tg::DST_AVG>(p, a, stream);
+    return launch_unpack<tg::SRC_CODES, tg::DST_AVG>(a, stream);
 }
 
 tg_status tg_unpack_update(tg_plan* p, int n_workers, const uint8_t* const* codes,
@@ -379,7 +379,7 @@ tg_status tg_unpack_update(tg_plan* p, int n_workers, const uint8_t* const* code
     a.s_shared = s_shared;
     a.avg = weights;
     a.eta = eta;
-    return launch_unpack<tg::SRC_CODES, tg::DST_UPDATE>(p, a, stream);
+    return launch_unpack<tg::SRC_CODES, tg::DST_UPDATE>(a, stream);
 }
 
 tg_status tg_unpack_update_momentum(tg_plan* p, int n_workers, const uint8_t* const* codes,
@@ -398,7 +398,7 @@ tg_status tg_unpack_update_momentum(tg_plan* p, int n_workers, const uint8_t* co
     a.velocity = velocity;
     a.eta = eta;
     a.mu = mu;
-    return launch_unpack<tg::SRC_CODES, tg::DST_MOMENTUM>(p, a, stream);
+    return launch_unpack<tg::SRC_CODES, tg::DST_MOMENTUM>(a, stream);
 }
 
 int64_t tg_sum_bytes(const tg_plan* p, int bits) {
@@ -419,8 +419,8 @@ tg_status tg_unpack_sum_pack(tg_plan* p, int n_workers, const uint8_t* const* co
     a.ksum_bytes = sum_bytes(p, bits);
     // the tiles must cover the pad fields too
     a.n_wave_tiles = (a.ksum_bytes * 8 / bits + tg::kWaveTile - 1) / tg::kWaveTile;
-    return bits == 4 ? launch_unpack<tg::SRC_CODES, tg::DST_K4>(p, a, stream)
-                     : launch_unpack<tg::SRC_CODES, tg::DST_K8>(p, a, stream);
+    return bits == 4 ? launch_unpack<tg::SRC_CODES, tg::DST_K4>(a, stream)
+                     : launch_unpack<tg::SRC_CODES, tg::DST_K8>(a, stream);
 }
 
 tg_status tg_decode_sum(tg_plan* p, int n_workers, const uint8_t* ksum, int bits,
@@ -438,8 +438,8 @@ tg_status tg_decode_sum(tg_plan* p, int n_workers, const uint8_t* ksum, int bits
     a.ksum_bytes = sum_bytes(p, bits);
     a.s_shared = s_shared;
     a.avg = avg;
-    return bits == 4 ? launch_unpack<tg::SRC_K4, tg::DST_AVG>(p, a, stream)
-                     : launch_unpack<tg::SRC_K8, tg::DST_AVG>(p, a, stream);
+    return bits == 4 ? launch_unpack<tg::SRC_K4, tg::DST_AVG>(a, stream)
+                     : launch_unpack<tg::SRC_K8, tg::DST_AVG>(a, stream);
 }
 
 tg_status tg_average_float(int n_workers, int64_t n, const float* const* grads, float* avg, void* stream) {

@@ -50,6 +50,7 @@ def test_plan_create_rejects_bad_tables_before_any_device_call(binding):
     assert _create(binding, [1, 5])[0] == binding.TG_ERR_INVALID_ARG          # off[0] != 0
     assert _create(binding, [0, 5, 3])[0] == binding.TG_ERR_INVALID_ARG       # not monotone
     assert _create(binding, [0, 0])[0] == binding.TG_ERR_INVALID_ARG          # n = 0
+    assert _create(binding, [0, (1 << 35) + 1])[0] == binding.TG_ERR_INVALID_ARG   # beyond TG_MAX_ELEMENTS
     assert _create(binding, [0, 8], 0)[0] == binding.TG_ERR_INVALID_ARG
     assert _create(binding, [0, 8], 65)[0] == binding.TG_ERR_TOO_MANY_WORKERS
     st = binding.lib.tg_plan_create(1, None, 1, ctypes.byref(ctypes.c_void_p()))

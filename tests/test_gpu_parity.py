@@ -271,6 +271,34 @@ def test_run_to_run_identical_statistics(binding):
         plan.close()
 
 
+def test_side_stream_and_one_worker_per_call(oracle, binding):
+    """calls are asynchronous on the caller's stream; n_workers = 1 with worker_base = rank (the
+    one-worker-per-GPU deployment) gives the same codes as the batched launch"""
+    rng = np.random.default_rng(41)
+    off = _off([30000, 17, 70000])
+    W = 3
+    grads = _grads(rng, off, W)
+    st = [oracle.clip_stats(g, off, 2.5) for g in grads]
+    tau = np.stack([x[0] for x in st])
+    s = oracle.share_scalers(np.stack([x[1] for x in st]))
+    want = [oracle.ternarize_pack(g, off, tau[w], s, 11, 2, 5 + w) for w, g in enumerate(grads)]
+    plan = binding.Plan(off, W)
+    side = torch.cuda.Stream()
+    try:
+        gd = [dev(g) for g in grads]
+        s_d = dev(s)
+        torch.cuda.synchronize()
+        nb = want[0].size
+        with torch.cuda.stream(side):
+            for w in range(W):
+                codes = torch.full((plan.packed_bytes,), 0xCD, dtype=torch.uint8, device="cuda")
+                plan.tg_ternarize_pack([gd[w]], dev(tau[w:w + 1]), s_d, 11, 2, [codes], worker_base=5 + w, stream=side)
+                side.synchronize()
+                assert np.array_equal(codes.cpu().numpy()[:nb], want[w])
+    finally:
+        plan.close()
+
+
 def test_argument_errors_on_device(binding):
     off = _off([100, 28])
     plan = binding.Plan(off, 2)

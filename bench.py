@@ -115,6 +115,27 @@ def main():
     torch.cuda.synchronize()
     ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
 
+    # the same step recorded once into a HIP graph and replayed (the iteration counter lives in device
+    # memory and is advanced by the graph's last node): what a launch-bound caller would do
+    step_dev = torch.zeros((1,), dtype=torch.int32, device="cuda")
+    side = torch.cuda.Stream()
+    side.wait_stream(stream)
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        plan.tg_clip_stats(grads, wl.clip_c, tau, s_local)
+        plan.tg_share_scalers(W, s_local, s_shared)
+        plan.tg_ternarize_pack_devstep(grads, tau, s_shared, wl.seed, step_dev, codes)
+        plan.tg_unpack_average(codes, s_shared, avg)
+        binding.tg_step_advance(step_dev, 1)
+    for _ in range(args.warmup):
+        graph.replay()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        graph.replay()
+    torch.cuda.synchronize()
+    ms_per_step_graph = (time.perf_counter() - t0) * 1e3 / args.steps
+
     # per-call timing with events on the launch stream, over K more steps
     evs = [[torch.cuda.Event(enable_timing=True) for _ in range(5)] for _ in range(args.steps)]
     for t in range(args.steps):
@@ -212,6 +233,7 @@ def main():
         "data": "synthetic",
         "config": {"workload": "%s gradients, fp32, W=%d simulated workers on one GPU, n=%d, L=%d, c=%.1f"
                                % (wl.name, W, n, L, wl.clip_c)},
+        "ms_per_step_graph_replay": round(ms_per_step_graph, 4),
         "kernels": kern, "roofline": roofline,
     }
 

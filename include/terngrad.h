@@ -139,6 +139,19 @@ tg_status tg_ternarize_pack(tg_plan* plan, int n_workers, uint32_t worker_base,
                             const float* const* grads, const float* tau, const float* s_shared,
                             uint64_t seed, uint32_t step, uint8_t* const* codes, void* stream);
 
+/* The same with the iteration counter t read from device memory at run time: a step recorded
+ * once into a HIP graph (these calls allocate nothing and never synchronise, so they can be
+ * captured) is replayed with a fresh random stream each time by advancing *step_dev between
+ * replays, e.g. with tg_step_advance as the graph's last node.  For the callers whose step is
+ * launch-bound (small models: five short launches).
+ *   step_dev  dev pointer to one uint32, 4-byte aligned, read by the kernel */
+tg_status tg_ternarize_pack_devstep(tg_plan* plan, int n_workers, uint32_t worker_base,
+                                    const float* const* grads, const float* tau, const float* s_shared,
+                                    uint64_t seed, const uint32_t* step_dev, uint8_t* const* codes, void* stream);
+
+/* *step_dev += by, as a one-thread kernel on `stream` (no memset or memcpy node is involved). */
+tg_status tg_step_advance(uint32_t* step_dev, uint32_t by, void* stream);
+
 /* Algorithm 1, server line: avg[e] = (sum_w t_w[e]) * (s_shared[layer(e)] / n_workers),
  * the integer sum exact, one fp32 division per layer and one fp32 product per element.
  *   codes     host array of n_workers dev pointers to code buffers, in

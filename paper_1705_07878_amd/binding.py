@@ -57,6 +57,11 @@ lib.tg_share_scalers.restype = ctypes.c_int
 lib.tg_ternarize_pack.argtypes = [_vp, ctypes.c_int, ctypes.c_uint32, _pp, _vp, _vp,
                                   ctypes.c_uint64, ctypes.c_uint32, _pp, _vp]
 lib.tg_ternarize_pack.restype = ctypes.c_int
+lib.tg_ternarize_pack_devstep.argtypes = [_vp, ctypes.c_int, ctypes.c_uint32, _pp, _vp, _vp,
+                                          ctypes.c_uint64, _vp, _pp, _vp]
+lib.tg_ternarize_pack_devstep.restype = ctypes.c_int
+lib.tg_step_advance.argtypes = [_vp, ctypes.c_uint32, _vp]
+lib.tg_step_advance.restype = ctypes.c_int
 lib.tg_unpack_average.argtypes = [_vp, ctypes.c_int, _pp, _vp, _vp, _vp]
 lib.tg_unpack_average.restype = ctypes.c_int
 lib.tg_unpack_update.argtypes = [_vp, ctypes.c_int, _pp, _vp, ctypes.c_float, _vp, _vp]
@@ -138,6 +143,10 @@ def tg_describe_tables(offsets):
 def tg_average_float(grads: Sequence, n: int, avg, stream=None):
     gp, _keep = _ptr_array(grads)
     _check(lib.tg_average_float(len(grads), int(n), gp, _ptr(avg), _stream(stream)), "tg_average_float")
+
+
+def tg_step_advance(step_dev, by: int = 1, stream=None):
+    _check(lib.tg_step_advance(_ptr(step_dev), int(by), _stream(stream)), "tg_step_advance")
 
 
 class Plan:
@@ -224,3 +233,13 @@ class Plan:
         _check(lib.tg_unpack_update_momentum(self._h, len(codes), cp, _ptr(s_shared), float(eta), float(mu),
                                              _ptr(velocity), _ptr(weights), _stream(stream)),
                "tg_unpack_update_momentum")
+
+    def tg_ternarize_pack_devstep(self, grads: Sequence, tau, s_shared, seed: int, step_dev, codes: Sequence,
+                                  worker_base: int = 0, stream=None):
+        gp, _k1 = _ptr_array(grads)
+        cp, _k2 = _ptr_array(codes)
+        if len(grads) != len(codes):
+            raise TgError(TG_ERR_INVALID_ARG, "tg_ternarize_pack_devstep")
+        _check(lib.tg_ternarize_pack_devstep(self._h, len(grads), int(worker_base), gp, _ptr(tau), _ptr(s_shared),
+                                             int(seed) & 0xFFFFFFFFFFFFFFFF, _ptr(step_dev), cp,
+                                             _stream(stream)), "tg_ternarize_pack_devstep")

@@ -321,9 +321,10 @@ tg_status tg_share_scalers(tg_plan* p, int n_workers, const float* s_local, floa
     return TG_OK;
 }
 
-tg_status tg_ternarize_pack(tg_plan* p, int n_workers, uint32_t worker_base,
-                            const float* const* grads, const float* tau, const float* s_shared,
-                            uint64_t seed, uint32_t step, uint8_t* const* codes, void* stream) {
+static tg_status ternarize_launch(tg_plan* p, int n_workers, uint32_t worker_base,
+                                  const float* const* grads, const float* tau, const float* s_shared,
+                                  uint64_t seed, uint32_t step, const uint32_t* step_dev,
+                                  uint8_t* const* codes, void* stream) {
     tg_status st = check_workers(p, n_workers);
     if (st != TG_OK) return st;
     if (grads == nullptr || codes == nullptr || tau == nullptr || s_shared == nullptr) return TG_ERR_INVALID_ARG;
@@ -346,10 +347,33 @@ tg_status tg_ternarize_pack(tg_plan* p, int n_workers, uint32_t worker_base,
     a.key0 = (uint32_t)seed;
     a.key1 = (uint32_t)(seed >> 32);
     a.step = step;
+    a.step_dev = step_dev;
     a.worker_base = worker_base;
     const int64_t blocks = (a.n_wave_tiles + tg::kBlock / tg::kWave - 1) / (tg::kBlock / tg::kWave);
     hipLaunchKernelGGL(tg::ternarize_pack_kernel, dim3((unsigned)blocks, (unsigned)n_workers),
                        dim3(tg::kBlock), 0, (hipStream_t)stream, a);
+    if (!hip_ok(hipGetLastError())) return TG_ERR_HIP;
+    return TG_OK;
+}
+
+tg_status tg_ternarize_pack(tg_plan* p, int n_workers, uint32_t worker_base,
+                            const float* const* grads, const float* tau, const float* s_shared,
+                            uint64_t seed, uint32_t step, uint8_t* const* codes, void* stream) {
+    return ternarize_launch(p, n_workers, worker_base, grads, tau, s_shared, seed, step, nullptr, codes, stream);
+}
+
+tg_status tg_ternarize_pack_devstep(tg_plan* p, int n_workers, uint32_t worker_base,
+                                    const float* const* grads, const float* tau, const float* s_shared,
+                                    uint64_t seed, const uint32_t* step_dev, uint8_t* const* codes, void* stream) {
+    if (step_dev == nullptr) return TG_ERR_INVALID_ARG;
+    if (!aligned(step_dev, 4)) return TG_ERR_ALIGNMENT;
+    return ternarize_launch(p, n_workers, worker_base, grads, tau, s_shared, seed, 0u, step_dev, codes, stream);
+}
+
+tg_status tg_step_advance(uint32_t* step_dev, uint32_t by, void* stream) {
+    if (step_dev == nullptr) return TG_ERR_INVALID_ARG;
+    if (!aligned(step_dev, 4)) return TG_ERR_ALIGNMENT;
+    hipLaunchKernelGGL(tg::step_advance_kernel, dim3(1), dim3(64), 0, (hipStream_t)stream, step_dev, by);
     if (!hip_ok(hipGetLastError())) return TG_ERR_HIP;
     return TG_OK;
 }

@@ -251,4 +251,9 @@ __global__ void share_scalers_kernel(const float* __restrict__ s_local, float* _
     s_shared[l] = m;                                                // Eq. 4
 }
 
+// iteration counter kept in device memory (see tg_ternarize_pack_devstep)
+__global__ void step_advance_kernel(uint32_t* step_dev, const uint32_t by) {
+    if (threadIdx.x == 0 && blockIdx.x == 0) *step_dev += by;
+}
+
 }  // namespace tg

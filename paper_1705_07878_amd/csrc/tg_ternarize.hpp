@@ -29,6 +29,8 @@ struct TernArgs {
     int64_t packed_bytes;       // ceil(n/4) rounded up to 16
     int32_t n_layers;
     uint32_t key0, key1, step, worker_base;
+    const uint32_t* step_dev;   // when not null the iteration counter is read from device memory
+                                // (so that a captured graph can be replayed with a new step)
 };
 
 // 8 code bits of 4 elements.  wa, wb: the two Philox words whose 16-bit halves
@@ -81,6 +83,7 @@ __global__ void __launch_bounds__(kBlock) ternarize_pack_kernel(const TernArgs p
     const int wave = wave_uniform(threadIdx.x >> 6);
     const uint32_t worker = p.worker_base + (uint32_t)w;
     const int par = lane & 1;
+    const uint32_t step = p.step_dev ? *p.step_dev : p.step;
 
     // one tile per wave: short-lived waves and a very large grid stream best here, and
     // without a loop every table lookup below is a scalar load
@@ -114,7 +117,7 @@ __global__ void __launch_bounds__(kBlock) ternarize_pack_kernel(const TernArgs p
 #pragma unroll
     for (int P = 0; P < 2; ++P) {
         const uint64_t qq = q + 64 * P;
-        const U4 R = philox4x32_10((uint32_t)qq, (uint32_t)(qq >> 32), worker, p.step, p.key0, p.key1);
+        const U4 R = philox4x32_10((uint32_t)qq, (uint32_t)(qq >> 32), worker, step, p.key0, p.key1);
         // quarter 2P: elements 8j..8j+7 belong to the even lane's block; the even lane
         // uses its words 0,1, the odd lane the even lane's words 2,3.  Quarter 2P+1:
         // the odd lane's block; the even lane takes its words 0,1, the odd lane keeps 2,3.

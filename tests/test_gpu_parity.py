@@ -299,6 +299,67 @@ def test_side_stream_and_one_worker_per_call(oracle, binding):
         plan.close()
 
 
+def test_whole_step_replayed_from_a_hip_graph(oracle, binding):
+    """the four calls (+ the step counter advance) captured once, replayed with eager work and
+    synchronisations in between; every replay equals the eager step with the same counter, and the
+    first one equals the oracle"""
+    from paper_1705_07878_amd import workloads
+    wl = workloads.lenet()
+    W, n, L, off = wl.n_workers, wl.n, wl.n_layers, wl.offsets
+    grads_np = [g.numpy() for g in workloads.make_gradients(wl, "cpu")]
+    plan = binding.Plan(off, W)
+    try:
+        gd = [dev(g) for g in grads_np]
+        tau = torch.empty((W, L), device="cuda")
+        sl = torch.empty((W, L), device="cuda")
+        ss = torch.empty((L,), device="cuda")
+        codes = [torch.zeros(plan.packed_bytes, dtype=torch.uint8, device="cuda") for _ in range(W)]
+        avg = torch.empty(n, device="cuda")
+        step0 = 40
+        step_dev = torch.tensor([step0], dtype=torch.int32, device="cuda")
+
+        def eager(step):
+            c = [torch.zeros(plan.packed_bytes, dtype=torch.uint8, device="cuda") for _ in range(W)]
+            a = torch.empty(n, device="cuda")
+            t2, s2, sh2 = torch.empty_like(tau), torch.empty_like(sl), torch.empty_like(ss)
+            plan.tg_clip_stats(gd, wl.clip_c, t2, s2)
+            plan.tg_share_scalers(W, s2, sh2)
+            plan.tg_ternarize_pack(gd, t2, sh2, 123, step, c)
+            plan.tg_unpack_average(c, sh2, a)
+            torch.cuda.synchronize()
+            return [x.cpu().numpy() for x in c], a.cpu().numpy(), t2.cpu().numpy(), sh2.cpu().numpy()
+
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):                      # warm-up on the capture stream
+            plan.tg_clip_stats(gd, wl.clip_c, tau, sl, stream=side)
+        side.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=side):
+            plan.tg_clip_stats(gd, wl.clip_c, tau, sl)
+            plan.tg_share_scalers(W, sl, ss)
+            plan.tg_ternarize_pack_devstep(gd, tau, ss, 123, step_dev, codes)
+            plan.tg_unpack_average(codes, ss, avg)
+            binding.tg_step_advance(step_dev, 1)
+        for i in range(4):
+            graph.replay()
+            torch.cuda.synchronize()
+            got_codes = [c.cpu().numpy() for c in codes]
+            got_avg = avg.cpu().numpy()
+            e_codes, e_avg, e_tau, e_s = eager(step0 + i)          # eager work between replays
+            for w in range(W):
+                assert np.array_equal(got_codes[w], e_codes[w]), (i, w)
+            assert np.array_equal(got_avg, e_avg), i
+            assert int(step_dev.item()) == step0 + i + 1
+            if i == 0:
+                nb = (n + 3) // 4
+                for w in range(W):
+                    want = oracle.ternarize_pack(grads_np[w], off, e_tau[w], e_s, 123, step0, w)
+                    assert np.array_equal(got_codes[w][:nb], want)
+    finally:
+        plan.close()
+
+
 def test_argument_errors_on_device(binding):
     off = _off([100, 28])
     plan = binding.Plan(off, 2)

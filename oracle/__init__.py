@@ -72,6 +72,12 @@ def lib() -> ctypes.CDLL:
         L.tgo_unpack_update_momentum.argtypes = [ctypes.POINTER(c_u8), ctypes.c_int, ctypes.c_int64, c_i64, c_f,
                                                  ctypes.c_float, ctypes.c_float, c_f, c_f]
         L.tgo_unpack_update_momentum.restype = None
+        L.tgo_ternarize_pack_base3.argtypes = L.tgo_ternarize_pack.argtypes
+        L.tgo_ternarize_pack_base3.restype = None
+        L.tgo_trit_at.argtypes = [c_u8, ctypes.c_int64]
+        L.tgo_trit_at.restype = ctypes.c_int
+        L.tgo_unpack_average_base3.argtypes = L.tgo_unpack_average.argtypes
+        L.tgo_unpack_average_base3.restype = None
         _lib = L
     return _lib
 
@@ -250,3 +256,39 @@ def unpack_update_momentum(codes_list, off, s_shared, eta, mu, velocity, weights
     assert v.size == n and w.size == n and s_shared.size == L
     lib().tgo_unpack_update_momentum(arr, len(keep), L, op, sp, np.float32(eta), np.float32(mu), _f32(v)[1], _f32(w)[1])
     return v, w
+
+
+def ternarize_pack_base3(g, off, tau, s_shared, seed, step, worker):
+    """-> uint8 [ceil(n/5)]: five ternary values per byte"""
+    g, gp = _f32(g)
+    off = _check_offsets(off, g.size)
+    _, op = _i64(off)
+    L = off.size - 1
+    tau, tp = _f32(tau)
+    s_shared, sp = _f32(s_shared)
+    assert tau.size == L and s_shared.size == L
+    codes = np.zeros((g.size + 4) // 5, np.uint8)
+    lib().tgo_ternarize_pack_base3(gp, L, op, tp, sp, int(seed), int(step), int(worker),
+                                   codes.ctypes.data_as(ctypes.POINTER(ctypes.c_uint8)))
+    return codes
+
+
+def trit_at(codes3, e: int) -> int:
+    codes3 = np.ascontiguousarray(codes3, dtype=np.uint8)
+    return int(lib().tgo_trit_at(codes3.ctypes.data_as(ctypes.POINTER(ctypes.c_uint8)), int(e)))
+
+
+def unpack_average_base3(codes_list, off, s_shared):
+    off = _check_offsets(off)
+    _, op = _i64(off)
+    L = off.size - 1
+    n = int(off[-1])
+    keep = [np.ascontiguousarray(c, dtype=np.uint8) for c in codes_list]
+    for c in keep:
+        assert c.size >= (n + 4) // 5
+    u8p = ctypes.POINTER(ctypes.c_uint8)
+    arr = (u8p * len(keep))(*[c.ctypes.data_as(u8p) for c in keep])
+    s_shared, sp = _f32(s_shared)
+    avg = np.empty(n, np.float32)
+    lib().tgo_unpack_average_base3(arr, len(keep), L, op, sp, _f32(avg)[1])
+    return avg

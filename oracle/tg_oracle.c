@@ -124,6 +124,18 @@ void tgo_share_scalers(const float* s_local, int n_workers, int64_t n_layers, fl
     }
 }
 
+/* Eq. 5, Eq. 3, Eq. 1 (without s) for one element: the ternary value t in {-1, 0, +1} */
+static int ternary_value(const float* g, int64_t e, int64_t n_layers, const int64_t* off,
+                         const float* tau, const float* s_shared,
+                         uint64_t seed, uint32_t step, uint32_t worker) {
+    const int64_t l = layer_of(e, n_layers, off);
+    const float ge = g[e];
+    const float a = fminf(fabsf(ge), tau[l]);                         /* Eq. 5 */
+    const uint32_t r = tgo_random_field(seed, step, worker, (uint64_t)e);
+    const int b = tgo_bernoulli(r, s_shared[l], a);                   /* Eq. 3 */
+    return b ? (signbit(ge) ? -1 : 1) : 0;                            /* Eq. 1 without s */
+}
+
 void tgo_ternarize_pack(const float* g, int64_t n_layers, const int64_t* off,
                         const float* tau, const float* s_shared,
                         uint64_t seed, uint32_t step, uint32_t worker, uint8_t* codes) {
@@ -136,12 +148,7 @@ void tgo_ternarize_pack(const float* g, int64_t n_layers, const int64_t* off,
         for (int j = 0; j < 4; ++j) {
             const int64_t e = 4 * byte + j;
             if (e >= n) break;                        /* pad codes stay 00 */
-            const int64_t l = layer_of(e, n_layers, off);
-            const float ge = g[e];
-            const float a = fminf(fabsf(ge), tau[l]);                 /* Eq. 5 */
-            const uint32_t r = tgo_random_field(seed, step, worker, (uint64_t)e);
-            const int b = tgo_bernoulli(r, s_shared[l], a);           /* Eq. 3 */
-            const int t = b ? (signbit(ge) ? -1 : 1) : 0;             /* Eq. 1 without s */
+            const int t = ternary_value(g, e, n_layers, off, tau, s_shared, seed, step, worker);
             packed |= ((unsigned)t & 3u) << (2 * j);
         }
         codes[byte] = (uint8_t)packed;
@@ -231,5 +238,42 @@ void tgo_unpack_update_momentum(const uint8_t* const* codes, int n_workers, int6
         const double v = (double)mu * (double)velocity[e] + avg;
         velocity[e] = (float)v;
         weights[e] = (float)((double)weights[e] - (double)eta * v);
+    }
+}
+
+void tgo_ternarize_pack_base3(const float* g, int64_t n_layers, const int64_t* off,
+                              const float* tau, const float* s_shared,
+                              uint64_t seed, uint32_t step, uint32_t worker, uint8_t* codes3) {
+    const int64_t n = off[n_layers];
+    const int64_t n_bytes = (n + 4) / 5;
+    #pragma omp parallel for num_threads(g_threads) schedule(static)
+    for (int64_t byte = 0; byte < n_bytes; ++byte) {
+        unsigned packed = 0, weight = 1;
+        for (int j = 0; j < 5; ++j, weight *= 3) {
+            const int64_t e = 5 * byte + j;
+            if (e >= n) break;                        /* pad digits stay 0 */
+            const int t = ternary_value(g, e, n_layers, off, tau, s_shared, seed, step, worker);
+            packed += weight * (unsigned)((t + 3) % 3);
+        }
+        codes3[byte] = (uint8_t)packed;
+    }
+}
+
+int tgo_trit_at(const uint8_t* codes3, int64_t e) {
+    unsigned v = codes3[e / 5] % 243u;
+    for (int j = 0; j < (int)(e % 5); ++j) v /= 3;
+    const int d = (int)(v % 3);
+    return d == 2 ? -1 : d;
+}
+
+void tgo_unpack_average_base3(const uint8_t* const* codes3, int n_workers, int64_t n_layers,
+                              const int64_t* off, const float* s_shared, float* avg) {
+    const int64_t n = off[n_layers];
+    #pragma omp parallel for num_threads(g_threads) schedule(static)
+    for (int64_t e = 0; e < n; ++e) {
+        const int64_t l = layer_of(e, n_layers, off);
+        long k = 0;
+        for (int w = 0; w < n_workers; ++w) k += tgo_trit_at(codes3[w], e);
+        avg[e] = (float)((double)k * (double)s_shared[l] / (double)n_workers);
     }
 }

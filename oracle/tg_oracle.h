@@ -95,6 +95,22 @@ void tgo_unpack_average(const uint8_t* const* codes, int n_workers, int64_t n_la
 void tgo_unpack_update(const uint8_t* const* codes, int n_workers, int64_t n_layers,
                        const int64_t* off, const float* s_shared, float eta, float* weights);
 
+/* Denser encoding toward the information bound 32/log2(3) = 20.18x of Section 3.1: five ternary
+ * values per byte (1.6 bits each, 20x).  Digit d = t mod 3 (0 -> 0, +1 -> 1, -1 -> 2); byte j holds
+ * elements 5j .. 5j+4 as d0 + 3*d1 + 9*d2 + 27*d3 + 81*d4 (0..242).  Same clip, same random field
+ * and same Bernoulli draw as tgo_ternarize_pack: the ternary values are identical, only the
+ * container differs.  Writes ceil(n/5) bytes; pad digits are 0. */
+void tgo_ternarize_pack_base3(const float* g, int64_t n_layers, const int64_t* off,
+                              const float* tau, const float* s_shared,
+                              uint64_t seed, uint32_t step, uint32_t worker, uint8_t* codes3);
+
+/* ternary value of element e of a base-3 buffer (a byte above 242 yields digits of byte mod 243) */
+int tgo_trit_at(const uint8_t* codes3, int64_t e);
+
+/* tgo_unpack_average over base-3 buffers. */
+void tgo_unpack_average_base3(const uint8_t* const* codes3, int n_workers, int64_t n_layers,
+                              const int64_t* off, const float* s_shared, float* avg);
+
 /* Layers kept in floating point (Section 4.2: the last classification layer is not
  * ternarized): the plain average avg_e = (float)( (sum_w (double)g_w[e]) / W ), summed in
  * worker order.  grads: W host pointers to n floats; avg: [n]. */

@@ -487,3 +487,40 @@ def test_momentum_update_matches_its_recurrence(oracle):
         v, w = oracle.unpack_update_momentum(codes, off, s, 0.0, 0.9, v, w)
     assert np.allclose(v, avg / (1 - np.float64(np.float32(0.9))), rtol=1e-5, atol=1e-9)
     assert np.array_equal(w, w0)
+
+
+# --------------------------------------------------------------------------
+# Section 3.1: toward the 32/log2(3) bound -- five ternary values per byte
+# --------------------------------------------------------------------------
+def test_base3_container_same_ternary_values(oracle):
+    rng = np.random.default_rng(22)
+    sizes = [7, 0, 131, 1, 64]
+    off = np.concatenate([[0], np.cumsum(sizes)])
+    n = int(off[-1])
+    g = (rng.normal(size=n) * 1e-2).astype(np.float32)
+    tau, s = oracle.clip_stats(g, off, 2.5)
+    c2 = oracle.ternarize_pack(g, off, tau, s, 5, 6, 7)
+    c3 = oracle.ternarize_pack_base3(g, off, tau, s, 5, 6, 7)
+    assert c3.size == (n + 4) // 5
+    t2 = decode(oracle, c2, n)
+    t3 = np.array([oracle.trit_at(c3, e) for e in range(n)])
+    assert np.array_equal(t2, t3)                                # same draws, other container
+    # byte value by its definition, digits 0 / 1 / 2 for 0 / +1 / -1, pad digits 0
+    d = np.concatenate([np.where(t2 < 0, 2, t2), np.zeros(5 * c3.size - n, dtype=np.int64)]).reshape(-1, 5)
+    assert np.array_equal(c3, (d * 3 ** np.arange(5)).sum(axis=1).astype(np.uint8))
+    assert np.array_equal(oracle.unpack_average_base3([c3, c3, c3], off, s), oracle.unpack_average([c2, c2, c2], off, s))
+    # 1.6 bits per value: 20x smaller than fp32, under the paper's bound of 20.18x
+    assert 32 / 1.6 <= 32 / math.log2(3) and abs(32 / 1.6 - PAPER["worker_to_server_reduction_ideal"]["value"]) < 0.2
+
+
+def test_base3_all_243_bytes(oracle):
+    for b in range(243):
+        digits = [(b // 3 ** m) % 3 for m in range(5)]
+        want = [-1 if x == 2 else x for x in digits]
+        buf = np.array([b], np.uint8)
+        assert [oracle.trit_at(buf, e) for e in range(5)] == want
+        t = np.array(want)
+        g = (t * 0.5).astype(np.float32)
+        got = oracle.ternarize_pack_base3(g, np.array([0, 5]), np.array([np.inf], np.float32),
+                                          np.array([0.5], np.float32), 1, 2, 3)
+        assert int(got[0]) == b

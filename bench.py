@@ -205,6 +205,23 @@ def main():
                                                         "pct_hbm_peak": round(100 * gbs / HBM_PEAK_GBS, 1)}
     del ksum
 
+    # Section 3.1, toward 32/log2(3): the base-3 container, five ternary values per byte (not in the step)
+    codes3 = [torch.empty((plan.packed_bytes_base3,), dtype=torch.uint8, device="cuda") for _ in range(W)]
+    for nm, fn, nbytes in (("ternarize_pack_base3", lambda: plan.tg_ternarize_pack_base3(grads, tau, s_shared, wl.seed, wl.step, codes3), W * 4.2),
+                           ("unpack_average_base3", lambda: plan.tg_unpack_average_base3(codes3, s_shared, avg), 0.2 * W + 4.0)):
+        for _ in range(2):
+            fn()
+        e0.record(stream)
+        for _ in range(reps):
+            fn()
+        e1.record(stream)
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / reps
+        gbs = n * nbytes / (ms * 1e-3) / 1e9
+        kern["%s (not in step)" % nm] = {"ms": round(ms, 4), "algorithmic_GBps": round(gbs, 1),
+                                         "pct_hbm_peak": round(100 * gbs / HBM_PEAK_GBS, 1)}
+    del codes3
+
     # Section 4.2 variant (not part of the timed step): plain fp32 average, as used for a layer that is
     # kept in floating point; timed here over the whole flat buffer to get a bandwidth figure
     favg = torch.empty((n,), dtype=torch.float32, device="cuda")

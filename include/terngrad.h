@@ -201,6 +201,20 @@ tg_status tg_unpack_sum_pack(tg_plan* plan, int n_workers, const uint8_t* const*
 tg_status tg_decode_sum(tg_plan* plan, int n_workers, const uint8_t* ksum, int bits,
                         const float* s_shared, float* avg, void* stream);
 
+/* Denser container, toward the bound 32/log2(3) = 20.18x of Section 3.1: five ternary values per
+ * byte (1.6 bits each, 20x smaller than fp32 instead of 16x).  Digit d = t mod 3 (0 -> 0, +1 -> 1,
+ * -1 -> 2); byte j holds elements 5j..5j+4 as d0 + 3 d1 + 9 d2 + 27 d3 + 81 d4.  Clip, random
+ * field and Bernoulli draw are those of tg_ternarize_pack: the ternary values are identical.
+ * A buffer holds tg_packed_bytes_base3(plan) = ceil(n/5) rounded up to 16 bytes, 4-byte aligned;
+ * pad digits and pad bytes are written as 0.  Arguments as for tg_ternarize_pack /
+ * tg_unpack_average. */
+int64_t tg_packed_bytes_base3(const tg_plan* plan);
+tg_status tg_ternarize_pack_base3(tg_plan* plan, int n_workers, uint32_t worker_base,
+                                  const float* const* grads, const float* tau, const float* s_shared,
+                                  uint64_t seed, uint32_t step, uint8_t* const* codes3, void* stream);
+tg_status tg_unpack_average_base3(tg_plan* plan, int n_workers, const uint8_t* const* codes3,
+                                  const float* s_shared, float* avg, void* stream);
+
 /* Layers kept in floating point.  Section 4.2 does not ternarize the last classification
  * layer; its gradients travel as fp32 and are averaged as such:
  *   avg[e] = (float)( (sum_w (double)grads[w][e]) / n_workers ),  e in [0, n)

@@ -74,6 +74,12 @@ lib.tg_unpack_sum_pack.argtypes = [_vp, ctypes.c_int, _pp, ctypes.c_int, _vp, _v
 lib.tg_unpack_sum_pack.restype = ctypes.c_int
 lib.tg_decode_sum.argtypes = [_vp, ctypes.c_int, _vp, ctypes.c_int, _vp, _vp, _vp]
 lib.tg_decode_sum.restype = ctypes.c_int
+lib.tg_packed_bytes_base3.argtypes = [_vp]
+lib.tg_packed_bytes_base3.restype = _i64
+lib.tg_ternarize_pack_base3.argtypes = lib.tg_ternarize_pack.argtypes
+lib.tg_ternarize_pack_base3.restype = ctypes.c_int
+lib.tg_unpack_average_base3.argtypes = lib.tg_unpack_average.argtypes
+lib.tg_unpack_average_base3.restype = ctypes.c_int
 lib.tg_average_float.argtypes = [ctypes.c_int, _i64, _pp, _vp, _vp]
 lib.tg_average_float.restype = ctypes.c_int
 
@@ -243,3 +249,22 @@ class Plan:
         _check(lib.tg_ternarize_pack_devstep(self._h, len(grads), int(worker_base), gp, _ptr(tau), _ptr(s_shared),
                                              int(seed) & 0xFFFFFFFFFFFFFFFF, _ptr(step_dev), cp,
                                              _stream(stream)), "tg_ternarize_pack_devstep")
+
+    @property
+    def packed_bytes_base3(self) -> int:
+        return int(lib.tg_packed_bytes_base3(self._h))
+
+    def tg_ternarize_pack_base3(self, grads: Sequence, tau, s_shared, seed: int, step: int, codes3: Sequence,
+                                worker_base: int = 0, stream=None):
+        gp, _k1 = _ptr_array(grads)
+        cp, _k2 = _ptr_array(codes3)
+        if len(grads) != len(codes3):
+            raise TgError(TG_ERR_INVALID_ARG, "tg_ternarize_pack_base3")
+        _check(lib.tg_ternarize_pack_base3(self._h, len(grads), int(worker_base), gp, _ptr(tau), _ptr(s_shared),
+                                           int(seed) & 0xFFFFFFFFFFFFFFFF, int(step) & 0xFFFFFFFF, cp,
+                                           _stream(stream)), "tg_ternarize_pack_base3")
+
+    def tg_unpack_average_base3(self, codes3: Sequence, s_shared, avg, stream=None):
+        cp, _k = _ptr_array(codes3)
+        _check(lib.tg_unpack_average_base3(self._h, len(codes3), cp, _ptr(s_shared), _ptr(avg),
+                                           _stream(stream)), "tg_unpack_average_base3")

@@ -321,10 +321,12 @@ tg_status tg_share_scalers(tg_plan* p, int n_workers, const float* s_local, floa
     return TG_OK;
 }
 
+static int64_t base3_bytes(const tg_plan* p) { return ((p->n + 4) / 5 + 15) / 16 * 16; }
+
 static tg_status ternarize_launch(tg_plan* p, int n_workers, uint32_t worker_base,
                                   const float* const* grads, const float* tau, const float* s_shared,
                                   uint64_t seed, uint32_t step, const uint32_t* step_dev,
-                                  uint8_t* const* codes, void* stream) {
+                                  uint8_t* const* codes, void* stream, bool base3 = false) {
     tg_status st = check_workers(p, n_workers);
     if (st != TG_OK) return st;
     if (grads == nullptr || codes == nullptr || tau == nullptr || s_shared == nullptr) return TG_ERR_INVALID_ARG;
@@ -349,6 +351,14 @@ static tg_status ternarize_launch(tg_plan* p, int n_workers, uint32_t worker_bas
     a.step = step;
     a.step_dev = step_dev;
     a.worker_base = worker_base;
+    if (base3) {
+        a.packed_bytes = base3_bytes(p);
+        const int64_t b3 = (a.packed_bytes + 1023) / 1024;
+        hipLaunchKernelGGL(tg::ternarize_pack_base3_kernel, dim3((unsigned)b3, (unsigned)n_workers),
+                           dim3(tg::kBase3Block), 0, (hipStream_t)stream, a);
+        if (!hip_ok(hipGetLastError())) return TG_ERR_HIP;
+        return TG_OK;
+    }
     const int64_t blocks = (a.n_wave_tiles + tg::kBlock / tg::kWave - 1) / (tg::kBlock / tg::kWave);
     hipLaunchKernelGGL(tg::ternarize_pack_kernel, dim3((unsigned)blocks, (unsigned)n_workers),
                        dim3(tg::kBlock), 0, (hipStream_t)stream, a);
@@ -368,6 +378,32 @@ tg_status tg_ternarize_pack_devstep(tg_plan* p, int n_workers, uint32_t worker_b
     if (step_dev == nullptr) return TG_ERR_INVALID_ARG;
     if (!aligned(step_dev, 4)) return TG_ERR_ALIGNMENT;
     return ternarize_launch(p, n_workers, worker_base, grads, tau, s_shared, seed, 0u, step_dev, codes, stream);
+}
+
+int64_t tg_packed_bytes_base3(const tg_plan* p) { return p ? base3_bytes(p) : -1; }
+
+tg_status tg_ternarize_pack_base3(tg_plan* p, int n_workers, uint32_t worker_base,
+                                  const float* const* grads, const float* tau, const float* s_shared,
+                                  uint64_t seed, uint32_t step, uint8_t* const* codes3, void* stream) {
+    return ternarize_launch(p, n_workers, worker_base, grads, tau, s_shared, seed, step, nullptr, codes3, stream, true);
+}
+
+tg_status tg_unpack_average_base3(tg_plan* p, int n_workers, const uint8_t* const* codes3,
+                                  const float* s_shared, float* avg, void* stream) {
+    tg_status st = check_workers(p, n_workers);
+    if (st != TG_OK) return st;
+    if (codes3 == nullptr || s_shared == nullptr || avg == nullptr) return TG_ERR_INVALID_ARG;
+    tg::UnpackArgs a{};
+    if ((st = fill_unpack(p, n_workers, codes3, a)) != TG_OK) return st;
+    if (!aligned(s_shared, 4) || !aligned(avg, 16)) return TG_ERR_ALIGNMENT;
+    a.s_shared = s_shared;
+    a.avg = avg;
+    a.packed_bytes = base3_bytes(p);
+    const int64_t blocks = (p->n + tg::kBase3Elems - 1) / tg::kBase3Elems;
+    hipLaunchKernelGGL((tg::unpack_average_base3_kernel<true, tg::DST_AVG>), dim3((unsigned)blocks),
+                       dim3(tg::kBase3Block), 0, (hipStream_t)stream, a);
+    if (!hip_ok(hipGetLastError())) return TG_ERR_HIP;
+    return TG_OK;
 }
 
 tg_status tg_step_advance(uint32_t* step_dev, uint32_t by, void* stream) {

@@ -11,6 +11,10 @@ constexpr int kBlock = 256;           // 4 waves per workgroup
 constexpr int kWaveTile = 1024;       // elements one wave handles per step: 64 lanes x 4 x float4
 constexpr int kTileShift = 12;        // tile_layer[] granularity: 4096 elements
 constexpr int kMaxWorkers = 64;
+// base-3 container (five ternary values per byte): a workgroup of five waves covers five tiles
+constexpr int kBase3Waves = 5;
+constexpr int kBase3Block = kBase3Waves * kWave;        // 320 threads
+constexpr int kBase3Elems = kBase3Waves * kWaveTile;    // 5120 elements <-> 1024 bytes
 
 // Philox4x32 (Salmon et al., SC'11), published multipliers and key increments.
 constexpr uint32_t kPhiloxM0 = 0xD2511F53u;

@@ -73,22 +73,14 @@ __device__ __forceinline__ uint32_t encode4v(const float4 v, const uint32_t wa, 
     return acc;
 }
 
-__global__ void __launch_bounds__(kBlock) ternarize_pack_kernel(const TernArgs p) {
-    __shared__ uint32_t lds[kBlock / kWave][kWave];   // 256 B per wave
-
-    const int w = blockIdx.y;
+// The code bytes of one 1024-element tile: b[k] = 2-bit codes of the lane's elements
+// 256k + 4*lane .. +3 (k = 0..3), for worker index w (of this call) and wave tile wt.
+__device__ __forceinline__ void tile_code_bytes(const TernArgs& p, const int w, const int64_t wt,
+                                                const int lane, uint32_t b[4]) {
     const float* __restrict__ g = p.grads[w];
-    uint8_t* __restrict__ codes = p.codes[w];
-    const int lane = threadIdx.x & (kWave - 1);
-    const int wave = wave_uniform(threadIdx.x >> 6);
     const uint32_t worker = p.worker_base + (uint32_t)w;
     const int par = lane & 1;
     const uint32_t step = p.step_dev ? *p.step_dev : p.step;
-
-    // one tile per wave: short-lived waves and a very large grid stream best here, and
-    // without a loop every table lookup below is a scalar load
-    const int64_t wt = (int64_t)blockIdx.x * (kBlock / kWave) + wave;
-    if (wt >= p.n_wave_tiles) return;
     const int64_t e0 = wt * kWaveTile;
 
     // the data loads depend on nothing but the tile index: issue them before the
@@ -100,7 +92,7 @@ __global__ void __launch_bounds__(kBlock) ternarize_pack_kernel(const TernArgs p
 #pragma unroll
         for (int k = 0; k < 4; ++k) v[k] = load_stream(gp + 256 * k);
     } else {
-        // ragged end of the buffer: elements past n read as 0, which encodes to 00
+        // ragged end of the buffer (or past it): missing elements read as 0, which encodes to 00
 #pragma unroll
         for (int k = 0; k < 4; ++k) {
             const int64_t e = e0 + 256 * k + 4 * lane;
@@ -127,10 +119,13 @@ __global__ void __launch_bounds__(kBlock) ternarize_pack_kernel(const TernArgs p
         rb[P][0] = par ? R.z : nx, rb[P][1] = par ? R.w : ny;
     }
 
+    if (e0 >= p.n) {   // a tile entirely past the end (only padding bytes to write)
+        b[0] = b[1] = b[2] = b[3] = 0u;
+        return;
+    }
     const int l0 = layer_from(p.off, p.n_layers, p.tile_layer[e0 >> kTileShift], e0);
     const bool whole = p.off[l0 + 1] >= e0 + kWaveTile || l0 + 1 >= p.n_layers;
     const float* __restrict__ tau_w = p.tau + (int64_t)w * p.n_layers;
-    uint32_t b[4];
 
     if (whole) {
         // ---- the tile lies inside layer l0 ----
@@ -169,6 +164,19 @@ __global__ void __launch_bounds__(kBlock) ternarize_pack_kernel(const TernArgs p
                            : encode4v(v[k], ra[P][0], ra[P][1], tau, s17);
         }
     }
+}
+
+__global__ void __launch_bounds__(kBlock) ternarize_pack_kernel(const TernArgs p) {
+    __shared__ uint32_t lds[kBlock / kWave][kWave];   // 256 B per wave
+
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wave = wave_uniform(threadIdx.x >> 6);
+    // one tile per wave: short-lived waves and a very large grid stream best here, and
+    // without a loop every table lookup is a scalar load
+    const int64_t wt = (int64_t)blockIdx.x * (kBlock / kWave) + wave;
+    if (wt >= p.n_wave_tiles) return;
+    uint32_t b[4];
+    tile_code_bytes(p, blockIdx.y, wt, lane, b);
 
     // ---- transpose bytes (position 64k + lane) into dwords (position 4*lane) ----
     uint8_t* row = reinterpret_cast<uint8_t*>(lds[wave]);
@@ -178,8 +186,48 @@ __global__ void __launch_bounds__(kBlock) ternarize_pack_kernel(const TernArgs p
     __builtin_amdgcn_wave_barrier();
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
     const uint32_t dw = lds[wave][lane];
-    const int64_t byte0 = (e0 >> 2) + 4 * lane;
-    if (byte0 < p.packed_bytes) store_through(reinterpret_cast<uint32_t*>(codes + byte0), dw);
+    const int64_t byte0 = (wt * kWaveTile >> 2) + 4 * lane;
+    if (byte0 < p.packed_bytes) store_through(reinterpret_cast<uint32_t*>(p.codes[blockIdx.y] + byte0), dw);
+}
+
+// ---- base-3 container: five ternary values per byte (1.6 bits, toward 32/log2(3)) ----
+// A workgroup of five waves encodes five tiles = 5120 elements exactly as above, leaves their
+// 1280 bytes of 2-bit codes in LDS, and 256 of its threads repack them: thread t turns 20
+// consecutive elements (40 bits) into four bytes d0 + 3 d1 + 9 d2 + 27 d3 + 81 d4 with digit
+// d = t mod 3 = code - (code >> 1).  1 KiB contiguous per workgroup.
+
+__device__ __forceinline__ uint32_t base3_byte(const uint32_t digits10) {
+    // five 2-bit digits (each 0..2) in bits 0..9
+    const uint32_t d0 = digits10 & 3u, d1 = (digits10 >> 2) & 3u, d2 = (digits10 >> 4) & 3u;
+    const uint32_t d3 = (digits10 >> 6) & 3u, d4 = (digits10 >> 8) & 3u;
+    return d0 + 3u * d1 + 9u * d2 + 27u * d3 + 81u * d4;
+}
+
+__global__ void __launch_bounds__(kBase3Block) ternarize_pack_base3_kernel(const TernArgs p) {
+    __shared__ uint32_t lds[kBase3Waves * kWave];       // 1280 B of 2-bit codes
+
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wave = wave_uniform(threadIdx.x >> 6);
+    const int64_t wt = (int64_t)blockIdx.x * kBase3Waves + wave;
+    uint32_t b[4];
+    tile_code_bytes(p, blockIdx.y, wt, lane, b);
+    uint8_t* bytes = reinterpret_cast<uint8_t*>(lds);
+#pragma unroll
+    for (int k = 0; k < 4; ++k) bytes[256 * wave + 64 * k + lane] = (uint8_t)b[k];
+    __syncthreads();
+
+    const int t = threadIdx.x;
+    if (t >= 256) return;
+    // elements 20t .. 20t+19 of the workgroup = 2-bit bytes 5t .. 5t+4
+    uint64_t x = 0;
+#pragma unroll
+    for (int j = 0; j < 5; ++j) x |= (uint64_t)bytes[5 * t + j] << (8 * j);
+    x -= (x >> 1) & 0x5555555555ull;                     // code 00/01/11 -> digit 0/1/2 in every field
+    uint32_t out = 0;
+#pragma unroll
+    for (int qd = 0; qd < 4; ++qd) out |= base3_byte((uint32_t)(x >> (10 * qd)) & 0x3FFu) << (8 * qd);
+    const int64_t byte0 = (int64_t)blockIdx.x * 1024 + 4 * t;
+    if (byte0 < p.packed_bytes) store_through(reinterpret_cast<uint32_t*>(p.codes[blockIdx.y] + byte0), out);
 }
 
 }  // namespace tg

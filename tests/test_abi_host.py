@@ -71,6 +71,9 @@ def test_null_plan_is_rejected(binding):
     assert binding.lib.tg_unpack_update_momentum(None, 1, None, None, 0.1, 0.9, None, None, None) == binding.TG_ERR_INVALID_ARG
     assert binding.lib.tg_ternarize_pack_devstep(None, 1, 0, None, None, None, 0, None, None, None) == binding.TG_ERR_INVALID_ARG
     assert binding.lib.tg_step_advance(None, 1, None) == binding.TG_ERR_INVALID_ARG
+    assert binding.lib.tg_packed_bytes_base3(None) == -1
+    assert binding.lib.tg_ternarize_pack_base3(None, 1, 0, None, None, None, 0, 0, None, None) == binding.TG_ERR_INVALID_ARG
+    assert binding.lib.tg_unpack_average_base3(None, 1, None, None, None, None) == binding.TG_ERR_INVALID_ARG
     assert binding.lib.tg_sum_bytes(None, 4) == -1
     assert binding.lib.tg_unpack_sum_pack(None, 1, None, 4, None, None) == binding.TG_ERR_INVALID_ARG
     assert binding.lib.tg_decode_sum(None, 1, None, 4, None, None, None) == binding.TG_ERR_INVALID_ARG

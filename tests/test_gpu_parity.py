@@ -240,6 +240,69 @@ def test_momentum_update(oracle, binding):
             plan.close()
 
 
+@pytest.mark.parametrize("sizes,W", [([1], 1), ([4], 2), ([5], 1), ([6], 1), ([1023], 1), ([1024], 2), ([5119], 1),
+                                     ([5120], 3), ([5121], 1), ([10240, 7, 0, 3000], 4), ([500, 20, 25000, 50, 400000, 500, 5000, 10], 2),
+                                     ([70001, 33333], 5), ([9000] * 7, 8), ([4099, 4093], 11)])
+def test_base3_container(oracle, binding, sizes, W):
+    """five ternary values per byte: encoder bit-exact (incl. padding), decoder within 1e-6 and
+    bit-identical to the 2-bit path on the same ternary values"""
+    rng = np.random.default_rng(abs(hash((tuple(sizes), W, 3))) % (2 ** 32))
+    off = _off(sizes)
+    n = int(off[-1])
+    grads = _grads(rng, off, W)
+    st = [oracle.clip_stats(g, off, 2.5) for g in grads]
+    tau = np.stack([x[0] for x in st])
+    s = oracle.share_scalers(np.stack([x[1] for x in st]))
+    want = [oracle.ternarize_pack_base3(g, off, tau[w], s, 31, 7, 2 + w) for w, g in enumerate(grads)]
+    plan = binding.Plan(off, W)
+    try:
+        pb = plan.packed_bytes_base3
+        assert pb == ((n + 4) // 5 + 15) // 16 * 16
+        codes = [torch.full((pb,), 0xCD, dtype=torch.uint8, device="cuda") for _ in range(W)]
+        plan.tg_ternarize_pack_base3([dev(g) for g in grads], dev(tau), dev(s), 31, 7, codes, worker_base=2)
+        torch.cuda.synchronize()
+        nb = (n + 4) // 5
+        for w in range(W):
+            got = codes[w].cpu().numpy()
+            assert np.array_equal(got[:nb], want[w]), (w, int(np.flatnonzero(got[:nb] != want[w])[0]))
+            assert not got[nb:].any()
+        cd = []
+        for c in want:
+            buf = np.zeros(pb, np.uint8)
+            buf[:c.size] = c
+            cd.append(dev(buf))
+        avg = torch.full((n,), float("nan"), dtype=torch.float32, device="cuda")
+        plan.tg_unpack_average_base3(cd, dev(s), avg)
+        torch.cuda.synchronize()
+        assert_avg_close(avg.cpu().numpy(), oracle.unpack_average_base3(want, off, s))
+        c2 = [oracle.ternarize_pack(g, off, tau[w], s, 31, 7, 2 + w) for w, g in enumerate(grads)]
+        assert np.array_equal(avg.cpu().numpy(), gpu_unpack_average(plan, c2, s))
+    finally:
+        plan.close()
+
+
+def test_base3_decoder_arbitrary_bytes(oracle, binding):
+    rng = np.random.default_rng(29)
+    off = _off([3000, 1, 6000, 1241])
+    n = int(off[-1])
+    for W in (1, 4, 5, 6, 11, 64):
+        codes = [rng.integers(0, 256, size=(n + 4) // 5, dtype=np.uint8) for _ in range(W)]
+        s = (np.abs(rng.normal(size=4)) + 0.01).astype(np.float32)
+        plan = binding.Plan(off, W)
+        try:
+            cd = []
+            for c in codes:
+                buf = np.zeros(plan.packed_bytes_base3, np.uint8)
+                buf[:c.size] = c
+                cd.append(dev(buf))
+            avg = torch.full((n,), float("nan"), dtype=torch.float32, device="cuda")
+            plan.tg_unpack_average_base3(cd, dev(s), avg)
+            torch.cuda.synchronize()
+            assert_avg_close(avg.cpu().numpy(), oracle.unpack_average_base3(codes, off, s))
+        finally:
+            plan.close()
+
+
 def test_extreme_scalers(oracle, binding):
     """tiny (subnormal threshold products), huge and zero scalers: same decisions on both sides"""
     rng = np.random.default_rng(10)

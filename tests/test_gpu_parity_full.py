@@ -82,6 +82,23 @@ def _full_config(oracle, binding, wl):
             assert np.array_equal(gc[:nb], oc), ("codes differ", w, int(np.flatnonzero(gc[:nb] != oc)[0]))
             assert not gc[nb:].any()
             o_codes.append(oc)
+        # ---- base-3 container at full size (skipped for the largest workload to bound the run time) ----
+        if n * W <= 1_200_000_000:
+            c3 = [torch.full((plan.packed_bytes_base3,), 0xCD, dtype=torch.uint8, device="cuda") for _ in range(W)]
+            plan.tg_ternarize_pack_base3(grads, dev(o_tau), dev(o_s), wl.seed, wl.step, c3)
+            torch.cuda.synchronize()
+            nb3 = (n + 4) // 5
+            o_c3 = []
+            for w in range(W):
+                oc = oracle.ternarize_pack_base3(grads[w].cpu().numpy(), off, o_tau[w], o_s, wl.seed, wl.step, w)
+                gc = c3[w].cpu().numpy()
+                assert np.array_equal(gc[:nb3], oc) and not gc[nb3:].any(), ("base-3 codes differ", w)
+                o_c3.append(oc)
+            a3 = torch.full((n,), float("nan"), dtype=torch.float32, device="cuda")
+            plan.tg_unpack_average_base3(c3, dev(o_s), a3)      # c3 equals the oracle's bytes (just checked)
+            torch.cuda.synchronize()
+            _avg_close_chunked(a3, oracle.unpack_average_base3(o_c3, off, o_s))
+            del c3, a3, o_c3
         # second moment at full size (Appendix A): non-zero codes ~ sum a/s, here just a sanity band
         nz = float(np.mean(np.unpackbits(o_codes[0][: 1 << 22]).reshape(-1, 2)[:, 1]))
         assert 0.05 < nz < 0.6

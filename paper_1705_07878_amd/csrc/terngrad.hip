@@ -302,9 +302,14 @@ tg_status tg_clip_stats(tg_plan* p, int n_workers, const float* const* grads, fl
     f.n_layers = (int32_t)p->n_layers;
     f.c = c;
     f.noclip = (!(c > 0.0f) || std::isinf(c)) ? 1 : 0;
-    const int64_t fblocks = (p->n_layers + tg::kBlock / tg::kWave - 1) / (tg::kBlock / tg::kWave);
-    hipLaunchKernelGGL(tg::clip_stats_final_kernel, dim3((unsigned)fblocks, (unsigned)n_workers),
-                       dim3(tg::kBlock), 0, s, f);
+    if (p->n_layers < tg::kFinalGroupedFrom) {
+        hipLaunchKernelGGL(tg::clip_stats_final_kernel, dim3((unsigned)p->n_layers, (unsigned)n_workers),
+                           dim3(tg::kFinalBlock), 0, s, f);
+    } else {
+        const int64_t fblocks = (p->n_layers + tg::kBlock / tg::kWave - 1) / (tg::kBlock / tg::kWave);
+        hipLaunchKernelGGL(tg::clip_stats_final_grouped_kernel, dim3((unsigned)fblocks, (unsigned)n_workers),
+                           dim3(tg::kBlock), 0, s, f);
+    }
     if (!hip_ok(hipGetLastError())) return TG_ERR_HIP;
     return TG_OK;
 }

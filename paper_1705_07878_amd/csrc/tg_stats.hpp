@@ -179,9 +179,48 @@ __device__ __forceinline__ void finish_layer(const StatsFinalArgs& p, const int 
     p.s_local[o] = fminf(m, tau);                               // Eq. 2 on the clipped layer
 }
 
-// A workgroup folds the partials of four consecutive layers: one wave per layer when all four are
-// small, else the whole workgroup layer after layer.  Fixed order either way.
-__global__ void __launch_bounds__(kBlock) clip_stats_final_kernel(const StatsFinalArgs p) {
+// Few layers (the networks of the paper): one workgroup of 1024 threads per layer and worker.
+constexpr int kFinalBlock = 1024;
+
+__global__ void __launch_bounds__(kFinalBlock) clip_stats_final_kernel(const StatsFinalArgs p) {
+    __shared__ double sh1[kFinalBlock / kWave], sh2[kFinalBlock / kWave];
+    __shared__ float shm[kFinalBlock / kWave];
+
+    const int l = blockIdx.x, w = blockIdx.y, t = threadIdx.x;
+    const int64_t sb = p.layer_seg[l], se = p.layer_seg[l + 1];
+    const int64_t base = (int64_t)w * p.n_segs;
+    Acc a = {0.0, 0.0, 0.0f};
+    for (int64_t i = sb + t; i < se; i += kFinalBlock) {
+        a.s1 += p.psum[base + i];
+        a.s2 += p.psq[base + i];
+        a.m = fmaxf(a.m, p.pmax[base + i]);
+    }
+    a = wave_reduce(a);
+    if ((t & 63) == 0) {
+        sh1[t >> 6] = a.s1;
+        sh2[t >> 6] = a.s2;
+        shm[t >> 6] = a.m;
+    }
+    __syncthreads();
+    if (t == 0) {
+        double s1 = sh1[0], s2 = sh2[0];
+        float m = shm[0];
+#pragma unroll
+        for (int k = 1; k < kFinalBlock / kWave; ++k) {
+            s1 += sh1[k];
+            s2 += sh2[k];
+            m = fmaxf(m, shm[k]);
+        }
+        finish_layer(p, l, w, s1, s2, m);
+    }
+}
+
+// Many layers (fine buckets): a workgroup folds the partials of four consecutive layers, one wave
+// per layer when all four are small, else the whole workgroup layer after layer.  Fixed order
+// either way.
+constexpr int kFinalGroupedFrom = 1024;   // layers
+
+__global__ void __launch_bounds__(kBlock) clip_stats_final_grouped_kernel(const StatsFinalArgs p) {
     __shared__ double sh1[kBlock / kWave], sh2[kBlock / kWave];
     __shared__ float shm[kBlock / kWave];
 

@@ -162,17 +162,38 @@ struct Emit {
     static constexpr bool MOMENTUM = DST == DST_MOMENTUM;
     static constexpr bool UPDATE = DST == DST_UPDATE || MOMENTUM;
     float4 wv[kSteps], vv[MOMENTUM ? kSteps : 1];
+    int l0s[kSteps];       // first layer of the tile written in step i
+    float scs[kSteps];     // its scale s/W ...
+    bool fast[kSteps];     // ... valid when the whole tile lies in that layer and inside the buffer
 
-    // the weights (and velocities) depend on nothing: their loads are issued first
+    // Everything that depends on nothing but the tile indices is fetched first, before the codes are
+    // summed and long before the barrier: the weights (and velocities), and the layer and scale of the
+    // tiles this wave will write.
     __device__ __forceinline__ void prefetch(const UnpackArgs& p, const int64_t tile0, const int wave, const int lane) {
-        if (!UPDATE) return;
+        const float fW = (float)p.n_workers;
 #pragma unroll
         for (int i = 0; i < kSteps; ++i) {
             const int q = wave + i * NWAVES;
-            const int64_t e = (tile0 + (q >> 2)) * kWaveTile + 256 * (q & 3) + 4 * lane;
-            if (e + 3 < p.n) {
-                wv[i] = load_stream(p.avg + e);
-                if (MOMENTUM) vv[i] = load_stream(p.velocity + e);
+            const int64_t tile = tile0 + (q >> 2);
+            const int64_t te0 = tile * kWaveTile;
+            if (UPDATE) {
+                const int64_t e = te0 + 256 * (q & 3) + 4 * lane;
+                if (e + 3 < p.n) {
+                    wv[i] = load_stream(p.avg + e);
+                    if (MOMENTUM) vv[i] = load_stream(p.velocity + e);
+                }
+            }
+            l0s[i] = 0;
+            scs[i] = 0.0f;
+            fast[i] = false;
+            if (tile < p.n_wave_tiles) {
+                const int l0 = layer_from(p.off, p.n_layers, p.tile_layer[te0 >> kTileShift], te0);
+                const bool one_layer = p.off[l0 + 1] >= te0 + kWaveTile || l0 + 1 >= p.n_layers;
+                l0s[i] = l0;
+                if (one_layer && te0 + kWaveTile <= p.n) {
+                    fast[i] = true;
+                    scs[i] = p.s_shared[l0] / fW;
+                }
             }
         }
     }
@@ -190,10 +211,9 @@ struct Emit {
             const int64_t te0 = tile * kWaveTile;
             const int64_t e = te0 + xq;
             const uint32_t d = kb[t][64 * (q & 3) + lane];
-            const int l0 = layer_from(p.off, p.n_layers, p.tile_layer[te0 >> kTileShift], te0);
-            const bool one_layer = p.off[l0 + 1] >= te0 + kWaveTile || l0 + 1 >= p.n_layers;
-            if (one_layer && te0 + kWaveTile <= p.n) {
-                float4 o = scale4(d, p.s_shared[l0] / fW);
+            const int l0 = l0s[i];
+            if (fast[i]) {
+                float4 o = scale4(d, scs[i]);
                 if (MOMENTUM) {
                     const float4 v = vv[i];
                     o = make_float4(__builtin_fmaf(p.mu, v.x, o.x), __builtin_fmaf(p.mu, v.y, o.y),

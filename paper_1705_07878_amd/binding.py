@@ -47,7 +47,8 @@ lib.tg_strerror.restype = ctypes.c_char_p
 lib.tg_last_hip_error.argtypes = []
 lib.tg_last_hip_error.restype = ctypes.c_int
 lib.tg_describe_tables.argtypes = [_i64, ctypes.POINTER(_i64),
-                                   ctypes.POINTER(_i64), ctypes.POINTER(_i64), ctypes.POINTER(ctypes.c_int32), _i64,
+                                   ctypes.POINTER(_i64), ctypes.POINTER(_i64), ctypes.POINTER(ctypes.c_int32),
+                                   ctypes.POINTER(ctypes.c_uint8), _i64,
                                    ctypes.POINTER(_i64), ctypes.POINTER(_i64), ctypes.POINTER(_i64), _i64]
 lib.tg_describe_tables.restype = ctypes.c_int
 lib.tg_clip_stats.argtypes = [_vp, ctypes.c_int, _pp, ctypes.c_float, _vp, _vp, _vp]
@@ -130,20 +131,22 @@ def tg_last_hip_error() -> int:
 
 
 def tg_describe_tables(offsets):
-    """-> dict(tile_elems, tile_layer[n_tiles], chunk_elems, segments[n_segs, 3])  (host only)"""
+    """-> dict(tile_elems, tile_layer[n_tiles], tile_whole[n_tiles], chunk_elems, segments[n_segs, 3])  (host only)"""
     off = np.ascontiguousarray(offsets, dtype=np.int64)
     L = off.size - 1
     offp = off.ctypes.data_as(ctypes.POINTER(_i64))
     te, nt, ce, ns = _i64(), _i64(), _i64(), _i64()
-    _check(lib.tg_describe_tables(L, offp, ctypes.byref(te), ctypes.byref(nt), None, 0,
+    _check(lib.tg_describe_tables(L, offp, ctypes.byref(te), ctypes.byref(nt), None, None, 0,
                                   ctypes.byref(ce), ctypes.byref(ns), None, 0), "tg_describe_tables")
     tl = np.empty(nt.value, np.int32)
+    tw = np.empty(nt.value, np.uint8)
     seg = np.empty((ns.value, 3), np.int64)
     _check(lib.tg_describe_tables(L, offp, ctypes.byref(te), ctypes.byref(nt),
-                                  tl.ctypes.data_as(ctypes.POINTER(ctypes.c_int32)), tl.size,
+                                  tl.ctypes.data_as(ctypes.POINTER(ctypes.c_int32)),
+                                  tw.ctypes.data_as(ctypes.POINTER(ctypes.c_uint8)), tl.size,
                                   ctypes.byref(ce), ctypes.byref(ns),
                                   seg.ctypes.data_as(ctypes.POINTER(_i64)), seg.shape[0]), "tg_describe_tables")
-    return {"tile_elems": te.value, "tile_layer": tl, "chunk_elems": ce.value, "segments": seg}
+    return {"tile_elems": te.value, "tile_layer": tl, "tile_whole": tw, "chunk_elems": ce.value, "segments": seg}
 
 
 def tg_average_float(grads: Sequence, n: int, avg, stream=None):

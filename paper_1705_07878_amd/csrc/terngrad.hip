@@ -29,9 +29,11 @@ bool hip_ok(hipError_t e) {
     return false;
 }
 
+constexpr int64_t kTilePad = 8;
+
 struct Tables {
     int64_t n = 0, n_tiles = 0, chunk = 0;
-    std::vector<int32_t> tile_layer;
+    std::vector<uint32_t> tile_info;  // [n_tiles + kTilePad]
     std::vector<int32_t> seg_layer;
     std::vector<int64_t> seg_begin, seg_end, seg_pivot;
     std::vector<int64_t> layer_seg;   // [L+1]
@@ -51,18 +53,25 @@ tg_status check_offsets(int64_t n_layers, const int64_t* off) {
 
 void build_tables(int64_t L, const int64_t* off, Tables& T) {
     const int64_t n = off[L];
-    const int64_t tile = (int64_t)1 << tg::kTileShift;
+    const int64_t tile = tg::kWaveTile;
     T.n = n;
     T.n_tiles = (n + tile - 1) / tile;
     T.chunk = n >= tg::kStatLargeFrom ? tg::kStatChunkLarge : tg::kStatChunk;
     const int64_t n_chunks = (n + T.chunk - 1) / T.chunk;
-    T.tile_layer.resize((size_t)T.n_tiles);
+    // One entry per wave tile: the layer of its first element, flagged when no other layer begins
+    // inside the tile (elements past n belong to nobody).  The kernels read their entry before they
+    // know whether the tile lies past the end, so a few padding entries follow (the code buffers are
+    // padded to 16 bytes and the base-3 kernel works in groups of five tiles).
+    T.tile_info.resize((size_t)(T.n_tiles + kTilePad));
     int64_t l = 0;
     for (int64_t t = 0; t < T.n_tiles; ++t) {
         const int64_t e = t * tile;
         while (e >= off[l + 1]) ++l;          // e < n = off[L]: stops at the layer that holds e
-        T.tile_layer[(size_t)t] = (int32_t)l;
+        const int64_t last = e + tile < n ? e + tile : n;
+        T.tile_info[(size_t)t] = (uint32_t)l | (off[l + 1] >= last ? tg::kTileWhole : 0u);
     }
+    for (int64_t t = T.n_tiles; t < T.n_tiles + kTilePad; ++t)
+        T.tile_info[(size_t)t] = (uint32_t)(L - 1) | tg::kTileWhole;
     T.layer_seg.assign((size_t)L + 1, 0);
     l = 0;
     int64_t next_layer_mark = 0;              // layers < this already have layer_seg set
@@ -116,7 +125,7 @@ struct tg_plan {
     int64_t n_layers = 0, n = 0, packed_bytes = 0, n_tiles = 0, n_segs = 0, n_units = 0;
     int max_workers = 0;
     int64_t* d_off = nullptr;
-    int32_t* d_tile_layer = nullptr;
+    uint32_t* d_tile_info = nullptr;
     int64_t* d_seg_begin = nullptr;
     int64_t* d_seg_end = nullptr;
     int64_t* d_seg_pivot = nullptr;
@@ -141,7 +150,7 @@ static tg_status launch_unpack(const tg::UnpackArgs& a, void* stream) {
 
 static tg_status fill_unpack(const tg_plan* p, int n_workers, const uint8_t* const* codes, tg::UnpackArgs& a) {
     a.off = p->d_off;
-    a.tile_layer = p->d_tile_layer;
+    a.tile_info = p->d_tile_info;
     a.n = p->n;
     a.n_wave_tiles = (p->n + tg::kWaveTile - 1) / tg::kWaveTile;
     a.packed_bytes = p->packed_bytes;
@@ -175,7 +184,7 @@ const char* tg_strerror(int status) {
 int tg_last_hip_error(void) { return g_last_hip_error; }
 
 tg_status tg_describe_tables(int64_t n_layers, const int64_t* offsets,
-                             int64_t* tile_elems, int64_t* n_tiles, int32_t* tile_layer, int64_t tile_cap,
+                             int64_t* tile_elems, int64_t* n_tiles, int32_t* tile_layer, uint8_t* tile_whole, int64_t tile_cap,
                              int64_t* chunk_elems, int64_t* n_segments, int64_t* seg, int64_t seg_cap) {
     const tg_status st = check_offsets(n_layers, offsets);
     if (st != TG_OK) return st;
@@ -185,12 +194,15 @@ tg_status tg_describe_tables(int64_t n_layers, const int64_t* offsets,
     } catch (const std::bad_alloc&) {
         return TG_ERR_ALLOC;
     }
-    if (tile_elems) *tile_elems = (int64_t)1 << tg::kTileShift;
+    if (tile_elems) *tile_elems = tg::kWaveTile;
     if (chunk_elems) *chunk_elems = T.chunk;
     if (n_tiles) *n_tiles = T.n_tiles;
     if (n_segments) *n_segments = (int64_t)T.seg_layer.size();
-    if (tile_layer && tile_cap >= T.n_tiles)
-        std::memcpy(tile_layer, T.tile_layer.data(), (size_t)T.n_tiles * sizeof(int32_t));
+    if (tile_cap >= T.n_tiles)
+        for (int64_t t = 0; t < T.n_tiles; ++t) {
+            if (tile_layer) tile_layer[t] = (int32_t)(T.tile_info[(size_t)t] & ~tg::kTileWhole);
+            if (tile_whole) tile_whole[t] = (T.tile_info[(size_t)t] & tg::kTileWhole) ? 1 : 0;
+        }
     if (seg && seg_cap >= (int64_t)T.seg_layer.size())
         for (size_t i = 0; i < T.seg_layer.size(); ++i) {
             seg[3 * i] = T.seg_layer[i];
@@ -226,7 +238,7 @@ tg_status tg_plan_create(int64_t n_layers, const int64_t* offsets, int max_worke
 
     const std::vector<int64_t> off(offsets, offsets + n_layers + 1);
     const size_t np = (size_t)p->n_segs * (size_t)max_workers;
-    bool ok = upload(&p->d_off, off) && upload(&p->d_tile_layer, T.tile_layer) &&
+    bool ok = upload(&p->d_off, off) && upload(&p->d_tile_info, T.tile_info) &&
               upload(&p->d_seg_begin, T.seg_begin) && upload(&p->d_seg_end, T.seg_end) &&
               upload(&p->d_seg_pivot, T.seg_pivot) && upload(&p->d_unit_first, T.unit_first) &&
               upload(&p->d_unit_count, T.unit_count) &&
@@ -245,7 +257,7 @@ tg_status tg_plan_create(int64_t n_layers, const int64_t* offsets, int max_worke
 
 tg_status tg_plan_destroy(tg_plan* p) {
     if (p == nullptr) return TG_OK;
-    void* bufs[] = {p->d_off, p->d_tile_layer, p->d_seg_begin, p->d_seg_end, p->d_seg_pivot, p->d_unit_first, p->d_unit_count,
+    void* bufs[] = {p->d_off, p->d_tile_info, p->d_seg_begin, p->d_seg_end, p->d_seg_pivot, p->d_unit_first, p->d_unit_count,
                     p->d_layer_seg, p->d_psum, p->d_psq, p->d_pmax};
     bool ok = true;
     for (void* b : bufs)
@@ -346,7 +358,7 @@ static tg_status ternarize_launch(tg_plan* p, int n_workers, uint32_t worker_bas
     a.tau = tau;
     a.s_shared = s_shared;
     a.off = p->d_off;
-    a.tile_layer = p->d_tile_layer;
+    a.tile_info = p->d_tile_info;
     a.n = p->n;
     a.packed_bytes = p->packed_bytes;
     a.n_wave_tiles = (p->packed_bytes * 4 + tg::kWaveTile - 1) / tg::kWaveTile;

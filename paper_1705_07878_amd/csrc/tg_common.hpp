@@ -9,7 +9,7 @@ namespace tg {
 constexpr int kWave = 64;             // CDNA wavefront
 constexpr int kBlock = 256;           // 4 waves per workgroup
 constexpr int kWaveTile = 1024;       // elements one wave handles per step: 64 lanes x 4 x float4
-constexpr int kTileShift = 12;        // tile_layer[] granularity: 4096 elements
+constexpr uint32_t kTileWhole = 0x80000000u;   // tile_info[]: flag "no layer boundary inside the tile"
 constexpr int kMaxWorkers = 64;
 // base-3 container (five ternary values per byte): a workgroup of five waves covers five tiles
 constexpr int kBase3Waves = 5;
@@ -88,11 +88,5 @@ __device__ __forceinline__ uint32_t swap_adjacent(uint32_t v) {
 }
 
 __device__ __forceinline__ int wave_uniform(int v) { return __builtin_amdgcn_readfirstlane(v); }
-
-// layer that holds flat element e, walking up from a layer known not to be past it
-__device__ __forceinline__ int layer_from(const int64_t* __restrict__ off, int n_layers, int l, int64_t e) {
-    while (l + 1 < n_layers && e >= off[l + 1]) ++l;
-    return l;
-}
 
 }  // namespace tg

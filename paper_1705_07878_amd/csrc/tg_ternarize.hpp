@@ -23,7 +23,7 @@ struct TernArgs {
     const float* tau;           // [W][L]
     const float* s_shared;      // [L]
     const int64_t* off;         // [L+1]
-    const int32_t* tile_layer;  // layer of element t << kTileShift
+    const uint32_t* tile_info;  // per wave tile: layer of its first element | kTileWhole
     int64_t n;
     int64_t n_wave_tiles;       // wave tiles that cover packed_bytes * 4 elements
     int64_t packed_bytes;       // ceil(n/4) rounded up to 16
@@ -80,11 +80,17 @@ __device__ __forceinline__ void tile_code_bytes(const TernArgs& p, const int w, 
     const float* __restrict__ g = p.grads[w];
     const uint32_t worker = p.worker_base + (uint32_t)w;
     const int par = lane & 1;
-    const uint32_t step = p.step_dev ? *p.step_dev : p.step;
+    // read through the constant address space: a scalar load either way.  (A generic load here
+    // would be a vector-memory operation ahead of the data loads, and the first use of the step,
+    // in the first Philox round, would then wait for the data as well.)
+    uint32_t step = p.step;
+    if (p.step_dev) step = *reinterpret_cast<const __attribute__((address_space(4))) uint32_t*>((uintptr_t)p.step_dev);
     const int64_t e0 = wt * kWaveTile;
 
     // the data loads depend on nothing but the tile index: issue them before the
-    // (dependent) table lookups so that the two latencies overlap
+    // (dependent) table lookups so that the two latencies overlap.  The table holds one entry per
+    // wave tile (also for the few padding tiles past the end), so the layer, the fast-path flag and
+    // with them tau and s are two scalar loads deep, all in flight while the random bits are computed.
     const bool inside = e0 + kWaveTile <= p.n;
     float4 v[4];
     if (inside) {
@@ -103,6 +109,13 @@ __device__ __forceinline__ void tile_code_bytes(const TernArgs& p, const int w, 
         }
     }
 
+    const uint32_t info = p.tile_info[wt];
+    const int l0 = (int)(info & ~kTileWhole);
+    const bool whole = (info & kTileWhole) != 0;
+    const float* __restrict__ tau_w = p.tau + (int64_t)w * p.n_layers;
+    const float tau0 = tau_w[l0];
+    const float s0 = p.s_shared[l0];
+
     // Philox blocks of this tile: q0 .. q0+127; lane computes q0 + 64P + 32*par + (lane>>1)
     uint32_t ra[2][2], rb[2][2];   // random words of quarters 2P (ra) and 2P+1 (rb)
     const uint64_t q = (uint64_t)(e0 >> 3) + (uint32_t)(32 * par + (lane >> 1));
@@ -119,18 +132,13 @@ __device__ __forceinline__ void tile_code_bytes(const TernArgs& p, const int w, 
         rb[P][0] = par ? R.z : nx, rb[P][1] = par ? R.w : ny;
     }
 
-    if (e0 >= p.n) {   // a tile entirely past the end (only padding bytes to write)
-        b[0] = b[1] = b[2] = b[3] = 0u;
-        return;
-    }
-    const int l0 = layer_from(p.off, p.n_layers, p.tile_layer[e0 >> kTileShift], e0);
-    const bool whole = p.off[l0 + 1] >= e0 + kWaveTile || l0 + 1 >= p.n_layers;
-    const float* __restrict__ tau_w = p.tau + (int64_t)w * p.n_layers;
-
+    // (a tile entirely past the end needs no special case: its elements read as 0 and its table
+    // entry names the last layer, so it encodes to zeros; an early exit here would only keep the
+    // table lookups from being scheduled alongside the Philox rounds)
     if (whole) {
         // ---- the tile lies inside layer l0 ----
-        const float tau = tau_w[l0];
-        const float s17 = p.s_shared[l0] * 0x1p-17f;
+        const float tau = tau0;
+        const float s17 = s0 * 0x1p-17f;
         const float s16 = s17 * 2.0f;
 #pragma unroll
         for (int P = 0; P < 2; ++P) {
@@ -156,8 +164,8 @@ __device__ __forceinline__ void tile_code_bytes(const TernArgs& p, const int w, 
             float tau[4], s17[4];
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
-                tau[i] = tau_w[l[i]];
-                s17[i] = p.s_shared[l[i]] * 0x1p-17f;
+                tau[i] = l[i] == l0 ? tau0 : tau_w[l[i]];
+                s17[i] = (l[i] == l0 ? s0 : p.s_shared[l[i]]) * 0x1p-17f;
             }
             const int P = k >> 1;
             b[k] = (k & 1) ? encode4v(v[k], rb[P][0], rb[P][1], tau, s17)

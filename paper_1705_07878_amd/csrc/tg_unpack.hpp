@@ -22,7 +22,7 @@ struct UnpackArgs {
     const uint8_t* codes[kMaxWorkers];
     const float* s_shared;      // [L]
     const int64_t* off;         // [L+1]
-    const int32_t* tile_layer;
+    const uint32_t* tile_info;  // per wave tile: layer of its first element | kTileWhole
     float* avg;                 // [n]: the average (out), or the weights (in/out) when updating
     float eta;                  // learning rate of the fused update
     float mu;                   // momentum of the fused update
@@ -187,8 +187,9 @@ struct Emit {
             scs[i] = 0.0f;
             fast[i] = false;
             if (tile < p.n_wave_tiles) {
-                const int l0 = layer_from(p.off, p.n_layers, p.tile_layer[te0 >> kTileShift], te0);
-                const bool one_layer = p.off[l0 + 1] >= te0 + kWaveTile || l0 + 1 >= p.n_layers;
+                const uint32_t info = p.tile_info[tile];
+                const int l0 = (int)(info & ~kTileWhole);
+                const bool one_layer = (info & kTileWhole) != 0;
                 l0s[i] = l0;
                 if (one_layer && te0 + kWaveTile <= p.n) {
                     fast[i] = true;

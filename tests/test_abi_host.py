@@ -86,6 +86,7 @@ def _brute_tables(off, tile, chunk):
     n = int(off[-1])
     lay = np.repeat(np.arange(off.size - 1), np.diff(off))
     tile_layer = lay[np.arange(0, n, tile)]
+    tile_whole = np.array([len(set(lay[e:e + tile])) == 1 for e in range(0, n, tile)], np.uint8)
     segs = []
     for cb in range(0, n, chunk):
         ce = min(n, cb + chunk)
@@ -95,7 +96,7 @@ def _brute_tables(off, tile, chunk):
             end = min(int(off[l + 1]), ce)
             segs.append((l, e, end))
             e = end
-    return tile_layer, np.array(segs, np.int64).reshape(-1, 3)
+    return tile_layer, tile_whole, np.array(segs, np.int64).reshape(-1, 3)
 
 
 @pytest.mark.parametrize("sizes", [[1], [4096], [4097], [16384, 16384], [5, 0, 0, 20000, 1, 40000, 3],
@@ -103,8 +104,9 @@ def _brute_tables(off, tile, chunk):
 def test_tables_match_brute_force(binding, sizes):
     off = np.concatenate([[0], np.cumsum(sizes)])
     d = binding.tg_describe_tables(off)
-    tl, segs = _brute_tables(off, d["tile_elems"], d["chunk_elems"])
+    tl, tw, segs = _brute_tables(off, d["tile_elems"], d["chunk_elems"])
     assert np.array_equal(d["tile_layer"], tl)
+    assert np.array_equal(d["tile_whole"], tw)
     assert np.array_equal(d["segments"], segs)
     # segments tile [0, n) exactly, in order, each inside one layer and one chunk
     s = d["segments"]

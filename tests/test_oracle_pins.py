@@ -238,6 +238,20 @@ def test_clip_stats_against_numpy_and_gaussian_closed_forms(oracle):
     assert lo <= angle <= hi
 
 
+def test_clip_stats_hand_computed_values(oracle):
+    # (3, -1, 1, 1): mean 1, deviations (2, -2, 0, 0), population variance 8/4 = 2 (a sample
+    # variance would be 8/3); (1, -1): sigma = 1; (0, 0, 6): mean 2, variance (4 + 4 + 16)/3 = 8
+    g = np.array([3, -1, 1, 1, 1, -1, 0, 0, 6], np.float32)
+    tau, s = oracle.clip_stats(g, np.array([0, 4, 6, 9]), 2.5)
+    assert tau[0] == np.float32(2.5 * math.sqrt(2.0)) and s[0] == 3.0
+    assert tau[1] == np.float32(2.5) and s[1] == 1.0
+    assert tau[2] == np.float32(2.5 * math.sqrt(8.0)) and s[2] == 6.0
+    # c = 1: the clip binds, the scaler is tau itself (Eq. 2 on the clipped layer)
+    tau, s = oracle.clip_stats(g, np.array([0, 4, 6, 9]), 1.0)
+    assert tau[0] == np.float32(math.sqrt(2.0)) and s[0] == tau[0]
+    assert tau[2] == np.float32(math.sqrt(8.0)) and s[2] == tau[2]
+
+
 def test_clip_stats_layerwise_and_edge_cases(oracle):
     rng = np.random.default_rng(9)
     sizes = [1, 2, 3, 0, 4, 5, 15, 16, 17, 1000]

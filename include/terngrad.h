@@ -222,8 +222,10 @@ tg_status tg_unpack_average_base3(tg_plan* plan, int n_workers, const uint8_t* c
  *   avg[e] = (float)( (sum_w (double)grads[w][e]) / n_workers ),  e in [0, n)
  * (fp64 sum in worker order, one rounding).  Needs no plan: the caller builds the plan over the
  * ternarized layers only and hands the float layers' slice of each flat buffer to this call.
- *   grads  host array of n_workers dev pointers, each to n fp32, 16-byte aligned
- *   avg    dev [n] fp32 out, 16-byte aligned */
+ *   grads  host array of n_workers dev pointers, each to n fp32
+ *   avg    dev [n] fp32 out
+ * The pointers need only be float addresses, but all of them (avg included) must be congruent
+ * modulo 16 bytes, as the same slice of equally laid out flat buffers is; else TG_ERR_ALIGNMENT. */
 tg_status tg_average_float(int n_workers, int64_t n, const float* const* grads, float* avg, void* stream);
 
 #ifdef __cplusplus

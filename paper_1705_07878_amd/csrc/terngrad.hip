@@ -523,17 +523,23 @@ tg_status tg_average_float(int n_workers, int64_t n, const float* const* grads, 
     if (n_workers < 1 || n < 1 || grads == nullptr || avg == nullptr) return TG_ERR_INVALID_ARG;
     if (n_workers > TG_MAX_WORKERS) return TG_ERR_TOO_MANY_WORKERS;
     tg::FloatAvgArgs a{};
+    // a float layer is usually a slice of a flat buffer: every pointer must be a float address and all
+    // must sit at the same position inside a 16-byte line, so that one shift aligns them together
+    if (!aligned(avg, 4)) return TG_ERR_ALIGNMENT;
+    const uintptr_t phase = ((uintptr_t)avg >> 2) & 3;
     for (int w = 0; w < n_workers; ++w) {
         if (grads[w] == nullptr) return TG_ERR_INVALID_ARG;
-        if (!aligned(grads[w], 16)) return TG_ERR_ALIGNMENT;
+        if (!aligned(grads[w], 4) || (((uintptr_t)grads[w] >> 2) & 3) != phase) return TG_ERR_ALIGNMENT;
         a.grads[w] = grads[w];
     }
-    if (!aligned(avg, 16)) return TG_ERR_ALIGNMENT;
     a.avg = avg;
     a.n = n;
     a.n_workers = n_workers;
-    const int64_t threads = (n + 3) / 4;
-    const int64_t blocks = (threads + tg::kBlock - 1) / tg::kBlock;
+    a.head = (int32_t)((4 - phase) & 3);
+    const int64_t body = n > a.head ? n - a.head : 0;
+    const int64_t threads = (body + 3) / 4;
+    int64_t blocks = (threads + tg::kBlock - 1) / tg::kBlock;
+    if (blocks < 1) blocks = 1;
     if (blocks > 0x7FFFFFFF) return TG_ERR_INVALID_ARG;
     hipLaunchKernelGGL(tg::average_float_kernel, dim3((unsigned)blocks), dim3(tg::kBlock), 0, (hipStream_t)stream, a);
     if (!hip_ok(hipGetLastError())) return TG_ERR_HIP;

@@ -13,12 +13,21 @@ struct FloatAvgArgs {
     float* avg;
     int64_t n;
     int32_t n_workers;
+    int32_t head;   // 0..3 leading elements before the first 16-byte boundary (the same for every buffer)
 };
 
+__device__ __forceinline__ void average_float_one(const FloatAvgArgs& p, const int64_t e, const double dW) {
+    double s = 0.0;
+    for (int w = 0; w < p.n_workers; ++w) s += (double)p.grads[w][e];
+    p.avg[e] = (float)(s / dW);
+}
+
 __global__ void __launch_bounds__(kBlock) average_float_kernel(const FloatAvgArgs p) {
-    const int64_t i = ((int64_t)blockIdx.x * kBlock + threadIdx.x) * 4;
-    if (i >= p.n) return;
+    const int64_t i = p.head + ((int64_t)blockIdx.x * kBlock + threadIdx.x) * 4;
     const double dW = (double)p.n_workers;
+    if (blockIdx.x == 0 && threadIdx.x == 0)
+        for (int64_t e = 0; e < p.head && e < p.n; ++e) average_float_one(p, e, dW);
+    if (i >= p.n) return;
     if (i + 3 < p.n) {
         double s0 = 0.0, s1 = 0.0, s2 = 0.0, s3 = 0.0;
         int w = 0;
@@ -45,11 +54,7 @@ __global__ void __launch_bounds__(kBlock) average_float_kernel(const FloatAvgArg
         __builtin_nontemporal_store(o.z, p.avg + i + 2);
         __builtin_nontemporal_store(o.w, p.avg + i + 3);
     } else {
-        for (int64_t e = i; e < p.n; ++e) {
-            double s = 0.0;
-            for (int w = 0; w < p.n_workers; ++w) s += (double)p.grads[w][e];
-            p.avg[e] = (float)(s / dW);
-        }
+        for (int64_t e = i; e < p.n; ++e) average_float_one(p, e, dW);
     }
 }
 

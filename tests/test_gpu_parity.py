@@ -145,7 +145,54 @@ def test_average_float_layers(oracle, binding):
         torch.cuda.synchronize()
         assert np.array_equal(out.cpu().numpy(), oracle.average_float(grads))
     with pytest.raises(binding.TgError):
-        binding.tg_average_float([out[1:]], 4, out)
+        binding.tg_average_float([out[1:]], 4, out)          # not congruent modulo 16 bytes
+
+
+def test_average_float_on_slices_of_flat_buffers(oracle, binding):
+    """a float layer is a slice of each worker's flat buffer: any float offset, the same in all"""
+    rng = np.random.default_rng(22)
+    for W, shift, n in ((2, 1, 1), (2, 1, 2), (3, 2, 3), (3, 3, 3), (2, 1, 4), (4, 3, 2051), (8, 2, 70_001), (2, 1, 1_000_003)):
+        flat = [(rng.normal(size=shift + n + 5) * 0.1).astype(np.float32) for _ in range(W)]
+        fd = [dev(f) for f in flat]
+        out = torch.full((shift + n + 5,), float("nan"), dtype=torch.float32, device="cuda")
+        binding.tg_average_float([f[shift:] for f in fd], n, out[shift:])
+        torch.cuda.synchronize()
+        got = out.cpu().numpy()
+        assert np.array_equal(got[shift:shift + n], oracle.average_float([f[shift:shift + n] for f in flat]))
+        assert np.isnan(got[:shift]).all() and np.isnan(got[shift + n:]).all()      # nothing outside the slice
+
+
+def test_last_layer_in_float(oracle, binding):
+    """Section 4.2 deployment: every layer ternarized except the last classification layer (weight and
+    bias), which travels and is averaged as fp32.  One flat gradient per worker; the plan covers the
+    ternarized prefix, the float call the rest of the same buffers."""
+    rng = np.random.default_rng(23)
+    sizes = [2400, 96, 51_203, 256, 100_001, 10, 4097 * 10, 10]      # ..., fc weight, fc bias
+    off = _off(sizes)
+    W, n, n_t = 4, int(off[-1]), int(off[-3])
+    grads = _grads(rng, off, W)
+    gd = [dev(g) for g in grads]
+    off_t = off[:-2]
+    r = full_parity(oracle, binding, off_t, [g[:n_t] for g in grads], step=5)
+    plan = binding.Plan(off_t, W)
+    # the ternarized prefix of the full buffers, fed the oracle's tau and s: the oracle's codes
+    codes = gpu_ternarize(plan, gd, r["tau"], r["s_shared"], 0, 5)
+    nb = (n_t + 3) // 4
+    for w in range(W):
+        assert np.array_equal(codes[w][:nb], r["codes"][w])
+    avg = torch.full((n,), float("nan"), dtype=torch.float32, device="cuda")
+    binding.tg_average_float([g[n_t:] for g in gd], n - n_t, avg[n_t:])          # first, so that a decoder
+    cd = []                                                                       # writing past n_t would show
+    for c in r["codes"]:
+        buf = np.zeros(plan.packed_bytes, np.uint8)
+        buf[:c.size] = c
+        cd.append(dev(buf))
+    plan.tg_unpack_average(cd, dev(r["s_shared"]), avg)
+    torch.cuda.synchronize()
+    got = avg.cpu().numpy()
+    assert np.array_equal(got[n_t:], oracle.average_float([g[n_t:] for g in grads]))
+    assert_avg_close(got[:n_t], r["avg"])
+    plan.close()
 
 
 @pytest.mark.parametrize("W,bits", [(1, 4), (2, 4), (4, 4), (7, 4), (4, 8), (8, 8), (11, 8), (64, 8)])

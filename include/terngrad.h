@@ -30,6 +30,14 @@
  *     worker_base = its rank.
  *   - Inputs must be finite; the result for NaN/Inf gradients is unspecified
  *     (never a fault).
+ *   - Threads and streams: a plan is immutable after creation except for the
+ *     reduction workspace that tg_clip_stats writes.  Calls on one plan may be
+ *     issued from any thread and on any stream, but two tg_clip_stats calls on
+ *     the same plan must not overlap on the device (order them on one stream or
+ *     with events, or use one plan per stream); all other calls only read the
+ *     plan.  A plan belongs to the device that was current at tg_plan_create and
+ *     must be used with streams of that device.  tg_plan_destroy does not wait
+ *     for work in flight: synchronise first.
  *
  * Definitions the paper leaves open (and this library fixes)
  *   - sigma is the population standard deviation of the layer, mean subtracted.

@@ -82,18 +82,28 @@ def assert_update_close(got, want, w0, avg):
     assert np.all(err <= REL * scale), float((err / np.maximum(scale, 1e-300)).max())
 
 
+def layer_max_abs(g, off):
+    """max |g| of every layer (0 for an empty one)"""
+    off = np.asarray(off, np.int64)
+    out = np.zeros(off.size - 1, np.float64)
+    full = np.flatnonzero(off[1:] > off[:-1])
+    if full.size:
+        out[full] = np.maximum.reduceat(np.abs(g), off[full])        # consecutive non-empty layers tile [0, n)
+    return out
+
+
 def assert_stats_close(got, want, grads_np, off, what):
     got = np.asarray(got, np.float64)
     want = np.asarray(want, np.float64)
+    assert got.shape == want.shape
     for w in range(want.shape[0]):
-        for l in range(want.shape[1]):
-            a, b = got[w, l], want[w, l]
-            if np.isinf(b):
-                assert a == b, (what, w, l, a, b)
-                continue
-            seg = grads_np[w][off[l]:off[l + 1]]
-            floor = REL * float(np.abs(seg).max()) if seg.size else 0.0
-            assert abs(a - b) <= max(REL * abs(b), floor), (what, w, l, a, b)
+        a, b = got[w], want[w]
+        inf = np.isinf(b)
+        assert np.array_equal(a[inf], b[inf]), (what, w)
+        floor = REL * layer_max_abs(grads_np[w], off)
+        af, bf = np.where(inf, 0.0, a), np.where(inf, 0.0, b)
+        bad = ~inf & ~(np.abs(af - bf) <= np.maximum(REL * np.abs(bf), floor))   # a NaN is bad too
+        assert not bad.any(), (what, w, int(np.flatnonzero(bad)[0]), a[bad][0], b[bad][0])
 
 
 def assert_avg_close(got, want):

@@ -113,6 +113,20 @@ def test_tables_match_brute_force(binding, sizes):
     assert s[0, 1] == 0 and s[-1, 2] == off[-1] and np.all(s[1:, 1] == s[:-1, 2]) and np.all(s[:, 2] > s[:, 1])
 
 
+def test_tables_at_the_layer_limit(binding):
+    # TG_MAX_LAYERS one-element layers: every layer its own segment, every tile full of boundaries
+    L = 1 << 22
+    off = np.arange(L + 1, dtype=np.int64)
+    d = binding.tg_describe_tables(off)
+    assert d["tile_elems"] == 1024 and d["tile_layer"].size == L // 1024
+    assert np.array_equal(d["tile_layer"], np.arange(0, L, 1024)) and not d["tile_whole"].any()
+    s = d["segments"]
+    assert s.shape == (L, 3) and np.array_equal(s[:, 0], off[:-1]) and np.array_equal(s[:, 1], off[:-1])
+    assert np.array_equal(s[:, 2], off[1:])
+    with pytest.raises(binding.TgError):
+        binding.tg_describe_tables(np.arange(L + 2, dtype=np.int64))        # one layer too many
+
+
 def test_binding_refuses_to_import_without_the_library(tmp_path):
     import subprocess
     import sys

@@ -56,6 +56,15 @@ def test_finer_buckets_than_a_layer(oracle, binding):
         full_parity(oracle, binding, off, _grads(rng, off, 2), seed=77, step=5)
 
 
+def test_many_tiny_layers(oracle, binding):
+    """hundreds of boundaries per tile, empty and one-element layers in runs, more than 1024 layers (the
+    grouped fold of the statistics) and a long layer in the middle"""
+    rng = np.random.default_rng(34)
+    sizes = list(rng.integers(0, 10, size=15_000)) + [70_001] + list(rng.integers(0, 4, size=5_000))
+    off = _off(sizes)
+    full_parity(oracle, binding, off, _grads(rng, off, 3), seed=9, step=1)
+
+
 def test_w64_and_worker_base(oracle, binding):
     rng = np.random.default_rng(64)
     off = _off([3000, 17, 5000])

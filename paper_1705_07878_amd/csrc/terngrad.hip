@@ -318,7 +318,7 @@ tg_status tg_clip_stats(tg_plan* p, int n_workers, const float* const* grads, fl
         hipLaunchKernelGGL(tg::clip_stats_final_kernel, dim3((unsigned)p->n_layers, (unsigned)n_workers),
                            dim3(tg::kFinalBlock), 0, s, f);
     } else {
-        const int64_t fblocks = (p->n_layers + tg::kBlock / tg::kWave - 1) / (tg::kBlock / tg::kWave);
+        const int64_t fblocks = (p->n_layers + tg::kBlock - 1) / tg::kBlock;
         hipLaunchKernelGGL(tg::clip_stats_final_grouped_kernel, dim3((unsigned)fblocks, (unsigned)n_workers),
                            dim3(tg::kBlock), 0, s, f);
     }

@@ -162,8 +162,6 @@ struct StatsFinalArgs {
     int32_t noclip;
 };
 
-constexpr int kFinalSmall = 64;   // layers with at most this many partials are folded by one wave
-
 __device__ __forceinline__ void finish_layer(const StatsFinalArgs& p, const int l, const int w,
                                              const double s1, const double s2, const float m) {
     const int64_t cnt = p.off[l + 1] - p.off[l];
@@ -215,69 +213,47 @@ __global__ void __launch_bounds__(kFinalBlock) clip_stats_final_kernel(const Sta
     }
 }
 
-// Many layers (fine buckets): a workgroup folds the partials of four consecutive layers, one wave
-// per layer when all four are small, else the whole workgroup layer after layer.  Fixed order
-// either way.
+// Many layers (fine buckets): a thread per layer.  A layer with a few partials is folded by its own
+// thread, one after the other; the layers of a wave that have more are then folded by the whole
+// wave, layer after layer (lanes strided over the partials, xor butterfly).  Which of the two a
+// layer gets depends on its number of partials alone, so the order of the additions is fixed.
 constexpr int kFinalGroupedFrom = 1024;   // layers
+constexpr int kFinalSerial = 8;           // partials a single thread folds
 
 __global__ void __launch_bounds__(kBlock) clip_stats_final_grouped_kernel(const StatsFinalArgs p) {
-    __shared__ double sh1[kBlock / kWave], sh2[kBlock / kWave];
-    __shared__ float shm[kBlock / kWave];
-
-    const int w = blockIdx.y, t = threadIdx.x, lane = t & 63;
-    const int wave = wave_uniform(t >> 6);
-    const int l_first = blockIdx.x * (kBlock / kWave);
+    const int w = blockIdx.y, lane = threadIdx.x & 63;
+    const int64_t l64 = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+    const bool have = l64 < p.n_layers;
+    const int l = have ? (int)l64 : 0;
     const int64_t base = (int64_t)w * p.n_segs;
-    const int lw = l_first + wave;
-    int64_t sb = 0, se = 0;
-    if (lw < p.n_layers) {
-        sb = p.layer_seg[lw];
-        se = p.layer_seg[lw + 1];
+    int sb = 0, se = 0;                         // fewer than 2^31 segments (elements / chunk + layers)
+    if (have) {
+        sb = (int)p.layer_seg[l];
+        se = (int)p.layer_seg[l + 1];
     }
-    const int any_large = __syncthreads_or(se - sb > kFinalSmall);
-
-    if (!any_large) {
-        if (lw >= p.n_layers) return;
+    const bool coop = se - sb > kFinalSerial;
+    if (have && !coop) {
         Acc a = {0.0, 0.0, 0.0f};
-        if (sb + lane < se) {
-            a.s1 = p.psum[base + sb + lane];
-            a.s2 = p.psq[base + sb + lane];
-            a.m = p.pmax[base + sb + lane];
+        for (int i = sb; i < se; ++i) {
+            a.s1 += p.psum[base + i];
+            a.s2 += p.psq[base + i];
+            a.m = fmaxf(a.m, p.pmax[base + i]);
         }
-        a = wave_reduce(a);
-        if (lane == 0) finish_layer(p, lw, w, a.s1, a.s2, a.m);
-        return;
+        finish_layer(p, l, w, a.s1, a.s2, a.m);
     }
-
-    for (int j = 0; j < kBlock / kWave; ++j) {
-        const int l = l_first + j;
-        if (l >= p.n_layers) break;
-        const int64_t b = p.layer_seg[l], e = p.layer_seg[l + 1];
+    unsigned long long todo = __ballot(coop);   // wave-uniform: every lane walks the same list
+    while (todo != 0ull) {
+        const int j = __ffsll((long long)todo) - 1;
+        todo &= todo - 1ull;
+        const int b = __shfl(sb, j, kWave), e = __shfl(se, j, kWave);
         Acc a = {0.0, 0.0, 0.0f};
-        for (int64_t i = b + t; i < e; i += kBlock) {
+        for (int i = b + lane; i < e; i += kWave) {
             a.s1 += p.psum[base + i];
             a.s2 += p.psq[base + i];
             a.m = fmaxf(a.m, p.pmax[base + i]);
         }
         a = wave_reduce(a);
-        if (lane == 0) {
-            sh1[wave] = a.s1;
-            sh2[wave] = a.s2;
-            shm[wave] = a.m;
-        }
-        __syncthreads();
-        if (t == 0) {
-            double s1 = sh1[0], s2 = sh2[0];
-            float m = shm[0];
-#pragma unroll
-            for (int k = 1; k < kBlock / kWave; ++k) {
-                s1 += sh1[k];
-                s2 += sh2[k];
-                m = fmaxf(m, shm[k]);
-            }
-            finish_layer(p, l, w, s1, s2, m);
-        }
-        __syncthreads();
+        if (lane == j) finish_layer(p, l, w, a.s1, a.s2, a.m);
     }
 }
 

@@ -58,9 +58,11 @@ def test_finer_buckets_than_a_layer(oracle, binding):
 
 def test_many_tiny_layers(oracle, binding):
     """hundreds of boundaries per tile, empty and one-element layers in runs, more than 1024 layers (the
-    grouped fold of the statistics) and a long layer in the middle"""
+    thread-per-layer fold of the statistics) and two long layers in between, one with few partials and
+    one with many"""
     rng = np.random.default_rng(34)
-    sizes = list(rng.integers(0, 10, size=15_000)) + [70_001] + list(rng.integers(0, 4, size=5_000))
+    sizes = (list(rng.integers(0, 10, size=100)) + [300_001] + list(rng.integers(0, 10, size=15_000)) + [70_001] +
+             list(rng.integers(0, 4, size=5_000)))
     off = _off(sizes)
     full_parity(oracle, binding, off, _grads(rng, off, 3), seed=9, step=1)
 

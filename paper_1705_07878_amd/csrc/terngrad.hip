@@ -37,8 +37,7 @@ struct Tables {
     std::vector<int32_t> seg_layer;
     std::vector<int64_t> seg_begin, seg_end, seg_pivot;
     std::vector<int64_t> layer_seg;   // [L+1]
-    std::vector<int64_t> unit_first;  // workgroups of the statistics pass
-    std::vector<int32_t> unit_count;
+    std::vector<tg::StatUnit> units;  // workgroups of the statistics pass
 };
 
 tg_status check_offsets(int64_t n_layers, const int64_t* off) {
@@ -95,17 +94,24 @@ void build_tables(int64_t L, const int64_t* off, Tables& T) {
     const int64_t n_segs = (int64_t)T.seg_layer.size();
     for (int64_t i = 0; i < n_segs;) {
         auto small = [&](int64_t k) { return T.seg_end[(size_t)k] - T.seg_begin[(size_t)k] <= tg::kSmallSeg; };
-        if (!small(i)) {
-            T.unit_first.push_back(i);
-            T.unit_count.push_back(0);
-            ++i;
-        } else {
-            int32_t cnt = 1;
+        tg::StatUnit u{};
+        int32_t cnt = 1, kind = 0;
+        if (small(i)) {
             while (cnt < tg::kBlock / tg::kWave && i + cnt < n_segs && small(i + cnt)) ++cnt;
-            T.unit_first.push_back(i);
-            T.unit_count.push_back(cnt);
-            i += cnt;
+            kind = cnt;
         }
+        for (int32_t j = 0; j < tg::kBlock / tg::kWave; ++j) {
+            // slot j is read by wave j: its own small segment, or the one large segment of the unit;
+            // unused slots keep an empty range and a valid pivot index
+            const int64_t k = kind == 0 ? i : (j < cnt ? i + j : -1);
+            u.slot[j].seg_kind = (k < 0 ? 0 : 8 * k) + kind;
+            if (k < 0) continue;
+            u.slot[j].begin = T.seg_begin[(size_t)k];
+            u.slot[j].end = T.seg_end[(size_t)k];
+            u.slot[j].pivot = T.seg_pivot[(size_t)k];
+        }
+        T.units.push_back(u);
+        i += cnt;
     }
 }
 
@@ -126,11 +132,7 @@ struct tg_plan {
     int max_workers = 0;
     int64_t* d_off = nullptr;
     uint32_t* d_tile_info = nullptr;
-    int64_t* d_seg_begin = nullptr;
-    int64_t* d_seg_end = nullptr;
-    int64_t* d_seg_pivot = nullptr;
-    int64_t* d_unit_first = nullptr;
-    int32_t* d_unit_count = nullptr;
+    tg::StatUnit* d_units = nullptr;
     int64_t* d_layer_seg = nullptr;
     double* d_psum = nullptr;
     double* d_psq = nullptr;
@@ -233,15 +235,13 @@ tg_status tg_plan_create(int64_t n_layers, const int64_t* offsets, int max_worke
     p->packed_bytes = (((T.n + 3) / 4) + 15) / 16 * 16;
     p->n_tiles = T.n_tiles;
     p->n_segs = (int64_t)T.seg_layer.size();
-    p->n_units = (int64_t)T.unit_first.size();
+    p->n_units = (int64_t)T.units.size();
     p->max_workers = max_workers;
 
     const std::vector<int64_t> off(offsets, offsets + n_layers + 1);
     const size_t np = (size_t)p->n_segs * (size_t)max_workers;
     bool ok = upload(&p->d_off, off) && upload(&p->d_tile_info, T.tile_info) &&
-              upload(&p->d_seg_begin, T.seg_begin) && upload(&p->d_seg_end, T.seg_end) &&
-              upload(&p->d_seg_pivot, T.seg_pivot) && upload(&p->d_unit_first, T.unit_first) &&
-              upload(&p->d_unit_count, T.unit_count) &&
+              upload(&p->d_units, T.units) &&
               upload(&p->d_layer_seg, T.layer_seg) &&
               hip_ok(hipMalloc((void**)&p->d_psum, np * sizeof(double))) &&
               hip_ok(hipMalloc((void**)&p->d_psq, np * sizeof(double))) &&
@@ -257,8 +257,7 @@ tg_status tg_plan_create(int64_t n_layers, const int64_t* offsets, int max_worke
 
 tg_status tg_plan_destroy(tg_plan* p) {
     if (p == nullptr) return TG_OK;
-    void* bufs[] = {p->d_off, p->d_tile_info, p->d_seg_begin, p->d_seg_end, p->d_seg_pivot, p->d_unit_first, p->d_unit_count,
-                    p->d_layer_seg, p->d_psum, p->d_psq, p->d_pmax};
+    void* bufs[] = {p->d_off, p->d_tile_info, p->d_units, p->d_layer_seg, p->d_psum, p->d_psq, p->d_pmax};
     bool ok = true;
     for (void* b : bufs)
         if (b != nullptr) ok = hip_ok(hipFree(b)) && ok;
@@ -288,11 +287,7 @@ tg_status tg_clip_stats(tg_plan* p, int n_workers, const float* const* grads, fl
         a.grads[w] = grads[w];
     }
     if (!aligned(tau, 4) || !aligned(s_local, 4)) return TG_ERR_ALIGNMENT;
-    a.unit_first = p->d_unit_first;
-    a.unit_count = p->d_unit_count;
-    a.seg_begin = p->d_seg_begin;
-    a.seg_end = p->d_seg_end;
-    a.seg_pivot = p->d_seg_pivot;
+    a.units = p->d_units;
     a.psum = p->d_psum;
     a.psq = p->d_psq;
     a.pmax = p->d_pmax;

@@ -21,13 +21,22 @@ constexpr int64_t kStatLargeFrom = (int64_t)1 << 27;
 
 constexpr int kSmallSeg = 2048;         // segments up to this size are reduced by one wave, four per workgroup
 
+// What one workgroup of the statistics pass reduces: a slot per wave, 32 contiguous bytes, so that
+// one scalar load gives a wave everything it needs to address its data.
+struct StatSlot {
+    int64_t begin, end;             // element range of the wave's segment (a large segment: the same in all four slots)
+    int64_t pivot;                  // index of the first element of that segment's layer
+    int64_t seg_kind;               // 8 * (index of the segment) + count; count 0: one large segment, block-wide;
+                                    // 1..4: the unit holds that many small segments, one per wave
+};
+struct StatUnit {
+    StatSlot slot[kBlock / kWave];
+};
+static_assert(sizeof(StatUnit) == 128, "one record = two cache lines of 64 bytes");
+
 struct StatsArgs {
     const float* grads[kMaxWorkers];
-    const int64_t* unit_first;      // [n_units] first segment of the workgroup's unit
-    const int32_t* unit_count;      // [n_units] 0: one large segment, block-wide; 1..4: that many small segments, one per wave
-    const int64_t* seg_begin;       // [n_segs]
-    const int64_t* seg_end;         // [n_segs]
-    const int64_t* seg_pivot;       // [n_segs] index of the first element of the segment's layer
+    const StatUnit* units;          // [n_units]
     double* psum;                   // [W][n_segs] sum (g - K)
     double* psq;                    // [W][n_segs] sum (g - K)^2
     float* pmax;                    // [W][n_segs] max |g|
@@ -64,9 +73,18 @@ __device__ __forceinline__ Acc wave_reduce(Acc a) {
     return a;
 }
 
+// The pivot as a double, converted where it is first needed.  The conversion is opaque to the
+// compiler so that it stays behind the data loads of the iteration it is in: the pivot itself is
+// still in flight when those are issued, and hoisting the conversion would wait for it first.
+__device__ __forceinline__ double pivot_value(const float Kf) {
+    double K;
+    asm volatile("v_cvt_f64_f32 %0, %1" : "=v"(K) : "v"(Kf));
+    return K;
+}
+
 // sums of one segment [b, e) over `nthr` cooperating threads (this thread is number t of them)
 __device__ __forceinline__ Acc segment_sums(const float* __restrict__ g, const int64_t b, const int64_t e,
-                                            const double K, const int t, const int nthr) {
+                                            const float Kf, const int t, const int nthr) {
     Acc a = {0.0, 0.0, 0.0f};
     const int64_t b4 = (b + 3) & ~(int64_t)3;
     const int64_t e4 = e & ~(int64_t)3;
@@ -78,16 +96,29 @@ __device__ __forceinline__ Acc segment_sums(const float* __restrict__ g, const i
         for (; i + 3 * nthr < nv; i += 4 * nthr) {
             const float4 v0 = load_stream(gp + 4 * i), v1 = load_stream(gp + 4 * (i + nthr));
             const float4 v2 = load_stream(gp + 4 * (i + 2 * nthr)), v3 = load_stream(gp + 4 * (i + 3 * nthr));
+            __builtin_amdgcn_sched_barrier(0);      // all four are issued before the first one is waited for
+            const double K = pivot_value(Kf);
             acc_add4(a, v0, K);
             acc_add4(a, v1, K);
             acc_add4(a, v2, K);
             acc_add4(a, v3, K);
         }
-        for (; i < nv; i += nthr) acc_add4(a, load_stream(gp + 4 * i), K);
+        // up to three groups are left for this thread: their loads are issued together as well
+        const bool h0 = i < nv, h1 = i + nthr < nv, h2 = i + 2 * nthr < nv;
+        float4 r0, r1, r2;
+        if (h0) r0 = load_stream(gp + 4 * i);
+        if (h1) r1 = load_stream(gp + 4 * (i + nthr));
+        if (h2) r2 = load_stream(gp + 4 * (i + 2 * nthr));
+        __builtin_amdgcn_sched_barrier(0);
+        const double K = pivot_value(Kf);
+        if (h0) acc_add4(a, r0, K);
+        if (h1) acc_add4(a, r1, K);
+        if (h2) acc_add4(a, r2, K);
         // ragged head and tail, at most 3 elements each
         if (t < b4 - b) acc_add(a, g[b + t], K);
         if (t < e - e4) acc_add(a, g[e4 + t], K);
     } else {
+        const double K = pivot_value(Kf);
         for (int64_t i = b + t; i < e; i += nthr) acc_add(a, g[i], K);
     }
     return a;
@@ -102,16 +133,25 @@ __global__ void __launch_bounds__(kBlock) clip_stats_partial_kernel(const StatsA
     const int w = blockIdx.y;
     const float* __restrict__ g = p.grads[w];
     const int t = threadIdx.x;
-    const int64_t first = p.unit_first[blockIdx.x];
-    const int count = p.unit_count[blockIdx.x];
+    // everything a wave needs comes from its slot of the unit record, whatever the kind of unit (the
+    // host repeats a large segment in all four slots): one load, which does not wait for the branch below
+    const int wave = wave_uniform(t >> 6);
+    const StatSlot& u = p.units[blockIdx.x].slot[wave];
+    const int64_t sg = u.seg_kind >> 3;
+    const int count = (int)(u.seg_kind & 7);
+    const int64_t sb = u.begin, se = u.end;
+    // the pivot travels through the vector memory path, like the data and ahead of it: results
+    // return in order, so waiting for it does not wait for the data loads issued behind it
+    // (a uniform address would become a scalar load; a zero the compiler cannot see through keeps it
+    // a vector load)
+    int lane_zero;
+    asm("v_mov_b32 %0, 0" : "=v"(lane_zero));
+    const float K = g[u.pivot + lane_zero];
 
     if (count > 0) {
         // small segments: wave j takes segment first + j
-        const int wave = wave_uniform(t >> 6);
         if (wave >= count) return;
-        const int64_t sg = first + wave;
-        const double K = (double)g[p.seg_pivot[sg]];
-        Acc a = segment_sums(g, p.seg_begin[sg], p.seg_end[sg], K, t & 63, kWave);
+        Acc a = segment_sums(g, sb, se, K, t & 63, kWave);
         a = wave_reduce(a);
         if ((t & 63) == 0) {
             const int64_t o = (int64_t)w * p.n_segs + sg;
@@ -122,9 +162,7 @@ __global__ void __launch_bounds__(kBlock) clip_stats_partial_kernel(const StatsA
         return;
     }
 
-    const int64_t sg = first;
-    const double K = (double)g[p.seg_pivot[sg]];
-    Acc a = segment_sums(g, p.seg_begin[sg], p.seg_end[sg], K, t, kBlock);
+    Acc a = segment_sums(g, sb, se, K, t, kBlock);
     a = wave_reduce(a);
     if ((t & 63) == 0) {
         sh1[t >> 6] = a.s1;

@@ -148,28 +148,41 @@ __device__ __forceinline__ void tile_code_bytes(const TernArgs& p, const int w, 
     } else {
         // ---- layers change inside the tile.  The layer of an element at tile position x is
         // l0 + #{ j > l0 : off[j] - e0 <= x }: one scalar pass over the (few) boundaries inside
-        // the tile, compared against all of the lane's positions at once; then tau and s are
-        // gathered per element.
+        // the tile, compared against all 16 positions of the lane at once.
+        int l[4][4];
+#pragma unroll
+        for (int k = 0; k < 4; ++k)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) l[k][i] = l0;
+        for (int j = l0 + 1; j < p.n_layers; ++j) {
+            const int64_t rel = p.off[j] - e0;
+            if (rel >= kWaveTile) break;
+            const int r = (int)rel;
+#pragma unroll
+            for (int k = 0; k < 4; ++k)
+#pragma unroll
+                for (int i = 0; i < 4; ++i) l[k][i] += (256 * k + 4 * lane + i >= r) ? 1 : 0;
+        }
 #pragma unroll
         for (int k = 0; k < 4; ++k) {
-            const int x0 = 256 * k + 4 * lane;
-            int l[4] = {l0, l0, l0, l0};
-            for (int j = l0 + 1; j < p.n_layers; ++j) {
-                const int64_t rel = p.off[j] - e0;
-                if (rel >= kWaveTile) break;
-                const int r = (int)rel;
-#pragma unroll
-                for (int i = 0; i < 4; ++i) l[i] += (x0 + i >= r) ? 1 : 0;
-            }
-            float tau[4], s17[4];
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                tau[i] = l[i] == l0 ? tau0 : tau_w[l[i]];
-                s17[i] = (l[i] == l0 ? s0 : p.s_shared[l[i]]) * 0x1p-17f;
-            }
             const int P = k >> 1;
-            b[k] = (k & 1) ? encode4v(v[k], rb[P][0], rb[P][1], tau, s17)
-                           : encode4v(v[k], ra[P][0], ra[P][1], tau, s17);
+            const uint32_t wa = (k & 1) ? rb[P][0] : ra[P][0], wb = (k & 1) ? rb[P][1] : ra[P][1];
+            if (__all(l[k][0] == l[k][3])) {
+                // no lane's four elements straddle a boundary (buckets that are multiples of four
+                // elements): one tau and one s per lane
+                const int ll = l[k][0];
+                const float tau = ll == l0 ? tau0 : tau_w[ll];
+                const float s17 = (ll == l0 ? s0 : p.s_shared[ll]) * 0x1p-17f;
+                b[k] = encode4(v[k], wa, wb, tau, s17 * 2.0f, s17);
+            } else {
+                float tau[4], s17[4];
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    tau[i] = l[k][i] == l0 ? tau0 : tau_w[l[k][i]];
+                    s17[i] = (l[k][i] == l0 ? s0 : p.s_shared[l[k][i]]) * 0x1p-17f;
+                }
+                b[k] = encode4v(v[k], wa, wb, tau, s17);
+            }
         }
     }
 }

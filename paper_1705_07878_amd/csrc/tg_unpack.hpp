@@ -199,6 +199,20 @@ struct Emit {
         }
     }
 
+    // the four elements at e (all inside the buffer) from their signed bytes d and one scale
+    __device__ __forceinline__ void emit4(const UnpackArgs& p, const int i, const int64_t e, const uint32_t d,
+                                          const float sc) const {
+        float4 o = scale4(d, sc);
+        if (MOMENTUM) {
+            const float4 v = vv[i];
+            o = make_float4(__builtin_fmaf(p.mu, v.x, o.x), __builtin_fmaf(p.mu, v.y, o.y),
+                            __builtin_fmaf(p.mu, v.z, o.z), __builtin_fmaf(p.mu, v.w, o.w));
+            store4<NT>(p.velocity + e, o);
+        }
+        if (UPDATE) o = apply4(wv[i], o, p.eta);
+        store4<NT>(p.avg + e, o);
+    }
+
     __device__ __forceinline__ void store(const UnpackArgs& p, const uint32_t (*kb)[kWaveTile / 4],
                                           const int64_t tile0, const int wave, const int lane) const {
         const float fW = (float)p.n_workers;
@@ -214,19 +228,11 @@ struct Emit {
             const uint32_t d = kb[t][64 * (q & 3) + lane];
             const int l0 = l0s[i];
             if (fast[i]) {
-                float4 o = scale4(d, scs[i]);
-                if (MOMENTUM) {
-                    const float4 v = vv[i];
-                    o = make_float4(__builtin_fmaf(p.mu, v.x, o.x), __builtin_fmaf(p.mu, v.y, o.y),
-                                    __builtin_fmaf(p.mu, v.z, o.z), __builtin_fmaf(p.mu, v.w, o.w));
-                    store4<NT>(p.velocity + e, o);
-                }
-                if (UPDATE) o = apply4(wv[i], o, p.eta);
-                store4<NT>(p.avg + e, o);
+                emit4(p, i, e, d, scs[i]);
             } else {
                 // layers change inside the tile, or the tile is ragged: the layer of the element at
                 // tile position x is l0 + #{ j > l0 : off[j] - te0 <= x } (one scalar pass over the
-                // boundaries inside the tile); one scale per element
+                // boundaries inside the tile)
                 int l[4] = {l0, l0, l0, l0};
                 for (int j = l0 + 1; j < p.n_layers; ++j) {
                     const int64_t rel = p.off[j] - te0;
@@ -235,6 +241,13 @@ struct Emit {
 #pragma unroll
                     for (int k = 0; k < 4; ++k) l[k] += (xq + k >= r) ? 1 : 0;
                 }
+                if (__all(l[0] == l[3] && e + 3 < p.n)) {
+                    // no lane's four elements straddle a boundary or the end (buckets that are
+                    // multiples of four elements): one scale per lane
+                    emit4(p, i, e, d, p.s_shared[l[0]] / fW);
+                    continue;
+                }
+                // one scale per element
                 const int di = (int)d;
                 const int kk[4] = {(int)(int8_t)di, (int)(int8_t)(di >> 8), (int)(int8_t)(di >> 16), di >> 24};
                 float o[4];

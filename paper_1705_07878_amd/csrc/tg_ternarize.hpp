@@ -33,19 +33,17 @@ struct TernArgs {
                                 // (so that a captured graph can be replayed with a new step)
 };
 
-// 8 code bits of 4 elements.  wa, wb: the two Philox words whose 16-bit halves
-// are the random fields of v.x, v.y (wa) and v.z, v.w (wb).
+// 8 code bits of 4 elements.  rf[i]: the 16-bit random field of element i, already a float.
 // threshold fl((2r+1) * s17) is formed as fma(r, 2*s17, s17): same real value,
 // one rounding.  Both sides of the comparison are non-negative floats, so the
 // order of their bit patterns as integers is their order as numbers.
-__device__ __forceinline__ uint32_t encode4(const float4 v, const uint32_t wa, const uint32_t wb,
+__device__ __forceinline__ uint32_t encode4(const float4 v, const float rf[4],
                                             const float tau, const float s16, const float s17) {
     const float g[4] = {v.x, v.y, v.z, v.w};
-    const uint32_t r[4] = {wa & 0xFFFFu, wa >> 16, wb & 0xFFFFu, wb >> 16};
     uint32_t acc = 0;
 #pragma unroll
     for (int i = 3; i >= 0; --i) {
-        const float thr = __builtin_fmaf((float)r[i], s16, s17);
+        const float thr = __builtin_fmaf(rf[i], s16, s17);
         const uint32_t gb = __float_as_uint(g[i]);
         const uint32_t ab = __float_as_uint(min_abs(g[i], tau));           // min(|g|, tau)
         const uint32_t d = __float_as_uint(thr) - ab;                       // bit 31 <=> thr < a
@@ -56,14 +54,13 @@ __device__ __forceinline__ uint32_t encode4(const float4 v, const uint32_t wa, c
 }
 
 // The same for 4 elements that may lie in different layers: per-element tau and s17.
-__device__ __forceinline__ uint32_t encode4v(const float4 v, const uint32_t wa, const uint32_t wb,
+__device__ __forceinline__ uint32_t encode4v(const float4 v, const float rf[4],
                                              const float tau[4], const float s17[4]) {
     const float g[4] = {v.x, v.y, v.z, v.w};
-    const uint32_t r[4] = {wa & 0xFFFFu, wa >> 16, wb & 0xFFFFu, wb >> 16};
     uint32_t acc = 0;
 #pragma unroll
     for (int i = 3; i >= 0; --i) {
-        const float thr = __builtin_fmaf((float)r[i], s17[i] * 2.0f, s17[i]);
+        const float thr = __builtin_fmaf(rf[i], s17[i] * 2.0f, s17[i]);
         const uint32_t gb = __float_as_uint(g[i]);
         const uint32_t ab = __float_as_uint(min_abs(g[i], tau[i]));
         const uint32_t d = __float_as_uint(thr) - ab;
@@ -117,7 +114,7 @@ __device__ __forceinline__ void tile_code_bytes(const TernArgs& p, const int w, 
     const float s0 = p.s_shared[l0];
 
     // Philox blocks of this tile: q0 .. q0+127; lane computes q0 + 64P + 32*par + (lane>>1)
-    uint32_t ra[2][2], rb[2][2];   // random words of quarters 2P (ra) and 2P+1 (rb)
+    float rf[4][4];                // random fields of the lane's elements, quarter k, as floats
     const uint64_t q = (uint64_t)(e0 >> 3) + (uint32_t)(32 * par + (lane >> 1));
 #pragma unroll
     for (int P = 0; P < 2; ++P) {
@@ -128,8 +125,13 @@ __device__ __forceinline__ void tile_code_bytes(const TernArgs& p, const int w, 
         // the odd lane's block; the even lane takes its words 0,1, the odd lane keeps 2,3.
         const uint32_t nx = swap_adjacent(R.x), ny = swap_adjacent(R.y);
         const uint32_t nz = swap_adjacent(R.z), nw = swap_adjacent(R.w);
-        ra[P][0] = par ? nz : R.x, ra[P][1] = par ? nw : R.y;
-        rb[P][0] = par ? R.z : nx, rb[P][1] = par ? R.w : ny;
+        const uint32_t a0 = par ? nz : R.x, a1 = par ? nw : R.y;     // quarter 2P
+        const uint32_t b0 = par ? R.z : nx, b1 = par ? R.w : ny;     // quarter 2P + 1
+        // converted here, ahead of the branch on the kind of tile and of the wait for the data
+        rf[2 * P][0] = (float)(a0 & 0xFFFFu), rf[2 * P][1] = (float)(a0 >> 16);
+        rf[2 * P][2] = (float)(a1 & 0xFFFFu), rf[2 * P][3] = (float)(a1 >> 16);
+        rf[2 * P + 1][0] = (float)(b0 & 0xFFFFu), rf[2 * P + 1][1] = (float)(b0 >> 16);
+        rf[2 * P + 1][2] = (float)(b1 & 0xFFFFu), rf[2 * P + 1][3] = (float)(b1 >> 16);
     }
 
     // (a tile entirely past the end needs no special case: its elements read as 0 and its table
@@ -141,47 +143,37 @@ __device__ __forceinline__ void tile_code_bytes(const TernArgs& p, const int w, 
         const float s17 = s0 * 0x1p-17f;
         const float s16 = s17 * 2.0f;
 #pragma unroll
-        for (int P = 0; P < 2; ++P) {
-            b[2 * P] = encode4(v[2 * P], ra[P][0], ra[P][1], tau, s16, s17);
-            b[2 * P + 1] = encode4(v[2 * P + 1], rb[P][0], rb[P][1], tau, s16, s17);
-        }
+        for (int k = 0; k < 4; ++k) b[k] = encode4(v[k], rf[k], tau, s16, s17);
     } else {
         // ---- layers change inside the tile.  The layer of an element at tile position x is
-        // l0 + #{ j > l0 : off[j] - e0 <= x }: one scalar pass over the (few) boundaries inside
-        // the tile, compared against all 16 positions of the lane at once.
-        int l[4][4];
-#pragma unroll
-        for (int k = 0; k < 4; ++k)
-#pragma unroll
-            for (int i = 0; i < 4; ++i) l[k][i] = l0;
-        for (int j = l0 + 1; j < p.n_layers; ++j) {
-            const int64_t rel = p.off[j] - e0;
-            if (rel >= kWaveTile) break;
-            const int r = (int)rel;
-#pragma unroll
-            for (int k = 0; k < 4; ++k)
-#pragma unroll
-                for (int i = 0; i < 4; ++i) l[k][i] += (256 * k + 4 * lane + i >= r) ? 1 : 0;
-        }
+        // l0 + #{ j > l0 : off[j] - e0 <= x }: a scalar pass over the (few) boundaries inside the
+        // tile per quarter (the table is read through the scalar cache; keeping all 16 positions of
+        // the lane live at once would cost the common path registers).
 #pragma unroll
         for (int k = 0; k < 4; ++k) {
-            const int P = k >> 1;
-            const uint32_t wa = (k & 1) ? rb[P][0] : ra[P][0], wb = (k & 1) ? rb[P][1] : ra[P][1];
-            if (__all(l[k][0] == l[k][3])) {
+            const int x0 = 256 * k + 4 * lane;
+            int l[4] = {l0, l0, l0, l0};
+            for (int j = l0 + 1; j < p.n_layers; ++j) {
+                const int64_t rel = p.off[j] - e0;
+                if (rel >= kWaveTile) break;
+                const int r = (int)rel;
+#pragma unroll
+                for (int i = 0; i < 4; ++i) l[i] += (x0 + i >= r) ? 1 : 0;
+            }
+            if (__all(l[0] == l[3])) {
                 // no lane's four elements straddle a boundary (buckets that are multiples of four
                 // elements): one tau and one s per lane
-                const int ll = l[k][0];
-                const float tau = ll == l0 ? tau0 : tau_w[ll];
-                const float s17 = (ll == l0 ? s0 : p.s_shared[ll]) * 0x1p-17f;
-                b[k] = encode4(v[k], wa, wb, tau, s17 * 2.0f, s17);
+                const float tau = l[0] == l0 ? tau0 : tau_w[l[0]];
+                const float s17 = (l[0] == l0 ? s0 : p.s_shared[l[0]]) * 0x1p-17f;
+                b[k] = encode4(v[k], rf[k], tau, s17 * 2.0f, s17);
             } else {
                 float tau[4], s17[4];
 #pragma unroll
                 for (int i = 0; i < 4; ++i) {
-                    tau[i] = l[k][i] == l0 ? tau0 : tau_w[l[k][i]];
-                    s17[i] = (l[k][i] == l0 ? s0 : p.s_shared[l[k][i]]) * 0x1p-17f;
+                    tau[i] = l[i] == l0 ? tau0 : tau_w[l[i]];
+                    s17[i] = (l[i] == l0 ? s0 : p.s_shared[l[i]]) * 0x1p-17f;
                 }
-                b[k] = encode4v(v[k], wa, wb, tau, s17);
+                b[k] = encode4v(v[k], rf[k], tau, s17);
             }
         }
     }

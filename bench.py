@@ -67,8 +67,20 @@ def cpu_baseline(wl, grads_host, sample_note):
     finally:
         oracle.set_threads(1)
     in_bytes = sum(g.size for g in grads_host) * 4.0
-    return {"value": in_bytes / dt / 1e9, "unit": "GB/s", "cores": used, "kind": "oracle",
-            "sample": "%s, mean of %d repetitions" % (sample_note, reps), "seconds": dt}
+    res = {"value": in_bytes / dt / 1e9, "unit": "GB/s", "cores": used, "kind": "oracle",
+           "sample": "%s, mean of %d repetitions" % (sample_note, reps), "seconds": dt}
+    # the same oracle on ONE thread, on a smaller sample: worker 0's clip_stats + ternarize_pack and
+    # its share of unpack_average (the decode of its own code buffer)
+    g0 = grads_host[0]
+    t0 = time.perf_counter()
+    tau0, s0 = oracle.clip_stats(g0, off, wl.clip_c)
+    c0 = oracle.ternarize_pack(g0, off, tau0, s0, wl.seed, wl.step, 0)
+    oracle.unpack_average([c0], off, s0)
+    dt1 = time.perf_counter() - t0
+    res["single_thread"] = {"value": round(g0.size * 4.0 / dt1 / 1e9, 3), "unit": "GB/s", "cores": 1,
+                            "sample": "worker 0 only: clip_stats, ternarize_pack, decode of its codes",
+                            "seconds": round(dt1, 2)}
+    return res
 
 
 def main():

@@ -110,9 +110,10 @@ int tg_last_hip_error(void);
  *   tile_whole[t]  = 1 when no other layer begins inside [t * tile, min((t+1) * tile, n)), else 0
  *   seg[3*i..]     = (layer, begin, end) of the i-th reduction segment: a maximal
  *                    run of elements inside one layer and one statistics chunk
- *                    of *chunk_elems elements
+ *                    of *chunk_elems elements (8192 to 65536, chosen from
+ *                    n * max_workers)
  * Pass NULL arrays (or too small capacities) to query the sizes only. */
-tg_status tg_describe_tables(int64_t n_layers, const int64_t* offsets,
+tg_status tg_describe_tables(int64_t n_layers, const int64_t* offsets, int max_workers,
                              int64_t* tile_elems, int64_t* n_tiles, int32_t* tile_layer, uint8_t* tile_whole,
                              int64_t tile_cap,
                              int64_t* chunk_elems, int64_t* n_segments, int64_t* seg, int64_t seg_cap);

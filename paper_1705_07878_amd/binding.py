@@ -46,7 +46,7 @@ lib.tg_strerror.argtypes = [ctypes.c_int]
 lib.tg_strerror.restype = ctypes.c_char_p
 lib.tg_last_hip_error.argtypes = []
 lib.tg_last_hip_error.restype = ctypes.c_int
-lib.tg_describe_tables.argtypes = [_i64, ctypes.POINTER(_i64),
+lib.tg_describe_tables.argtypes = [_i64, ctypes.POINTER(_i64), ctypes.c_int,
                                    ctypes.POINTER(_i64), ctypes.POINTER(_i64), ctypes.POINTER(ctypes.c_int32),
                                    ctypes.POINTER(ctypes.c_uint8), _i64,
                                    ctypes.POINTER(_i64), ctypes.POINTER(_i64), ctypes.POINTER(_i64), _i64]
@@ -130,18 +130,18 @@ def tg_last_hip_error() -> int:
     return int(lib.tg_last_hip_error())
 
 
-def tg_describe_tables(offsets):
+def tg_describe_tables(offsets, max_workers: int = 1):
     """-> dict(tile_elems, tile_layer[n_tiles], tile_whole[n_tiles], chunk_elems, segments[n_segs, 3])  (host only)"""
     off = np.ascontiguousarray(offsets, dtype=np.int64)
     L = off.size - 1
     offp = off.ctypes.data_as(ctypes.POINTER(_i64))
     te, nt, ce, ns = _i64(), _i64(), _i64(), _i64()
-    _check(lib.tg_describe_tables(L, offp, ctypes.byref(te), ctypes.byref(nt), None, None, 0,
+    _check(lib.tg_describe_tables(L, offp, int(max_workers), ctypes.byref(te), ctypes.byref(nt), None, None, 0,
                                   ctypes.byref(ce), ctypes.byref(ns), None, 0), "tg_describe_tables")
     tl = np.empty(nt.value, np.int32)
     tw = np.empty(nt.value, np.uint8)
     seg = np.empty((ns.value, 3), np.int64)
-    _check(lib.tg_describe_tables(L, offp, ctypes.byref(te), ctypes.byref(nt),
+    _check(lib.tg_describe_tables(L, offp, int(max_workers), ctypes.byref(te), ctypes.byref(nt),
                                   tl.ctypes.data_as(ctypes.POINTER(ctypes.c_int32)),
                                   tw.ctypes.data_as(ctypes.POINTER(ctypes.c_uint8)), tl.size,
                                   ctypes.byref(ce), ctypes.byref(ns),

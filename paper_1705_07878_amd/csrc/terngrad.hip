@@ -50,12 +50,12 @@ tg_status check_offsets(int64_t n_layers, const int64_t* off) {
     return TG_OK;
 }
 
-void build_tables(int64_t L, const int64_t* off, Tables& T) {
+void build_tables(int64_t L, const int64_t* off, int max_workers, Tables& T) {
     const int64_t n = off[L];
     const int64_t tile = tg::kWaveTile;
     T.n = n;
     T.n_tiles = (n + tile - 1) / tile;
-    T.chunk = n >= tg::kStatLargeFrom ? tg::kStatChunkLarge : tg::kStatChunk;
+    T.chunk = tg::stat_chunk(n * (int64_t)max_workers);
     const int64_t n_chunks = (n + T.chunk - 1) / T.chunk;
     // One entry per wave tile: the layer of its first element, flagged when no other layer begins
     // inside the tile (elements past n belong to nobody).  The kernels read their entry before they
@@ -185,14 +185,15 @@ const char* tg_strerror(int status) {
 
 int tg_last_hip_error(void) { return g_last_hip_error; }
 
-tg_status tg_describe_tables(int64_t n_layers, const int64_t* offsets,
+tg_status tg_describe_tables(int64_t n_layers, const int64_t* offsets, int max_workers,
                              int64_t* tile_elems, int64_t* n_tiles, int32_t* tile_layer, uint8_t* tile_whole, int64_t tile_cap,
                              int64_t* chunk_elems, int64_t* n_segments, int64_t* seg, int64_t seg_cap) {
     const tg_status st = check_offsets(n_layers, offsets);
     if (st != TG_OK) return st;
+    if (max_workers < 1 || max_workers > TG_MAX_WORKERS) return TG_ERR_INVALID_ARG;
     Tables T;
     try {
-        build_tables(n_layers, offsets, T);
+        build_tables(n_layers, offsets, max_workers, T);
     } catch (const std::bad_alloc&) {
         return TG_ERR_ALLOC;
     }
@@ -225,7 +226,7 @@ tg_status tg_plan_create(int64_t n_layers, const int64_t* offsets, int max_worke
     Tables T;
     tg_plan* p = nullptr;
     try {
-        build_tables(n_layers, offsets, T);
+        build_tables(n_layers, offsets, max_workers, T);
         p = new tg_plan();
     } catch (const std::bad_alloc&) {
         return TG_ERR_ALLOC;

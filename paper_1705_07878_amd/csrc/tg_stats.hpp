@@ -3,8 +3,8 @@
 // max|clip(g)| = min(max|g|, c*sigma), so sigma and the scaler come out of the
 // same pass.  Sums are fp64 and taken about a per-layer pivot K = first element
 // of the layer (shifted-data variance: exact for a constant layer, insensitive to
-// a large mean).  No float atomics: every statistics chunk (16384 elements, 65536 for
-// gradients beyond 2^27 elements) is cut into segments, one per layer it touches; a
+// a large mean).  No float atomics: every statistics chunk (8192 to 65536 elements, by the size of
+// the job) is cut into segments, one per layer it touches; a
 // workgroup reduces one large segment (or four small ones, a wave each) in a fixed tree and
 // writes one partial per segment; a second small kernel folds the partials of each layer in
 // a fixed order.  Results are bit-identical from
@@ -15,9 +15,15 @@
 
 namespace tg {
 
-constexpr int kStatChunk = 16384;       // elements per workgroup: 256 threads x 16 float4
-constexpr int kStatChunkLarge = 65536;  // for very large gradients (fewer partials to fold)
-constexpr int64_t kStatLargeFrom = (int64_t)1 << 27;
+// elements per statistics chunk (a workgroup reduces at most one chunk): 256 threads x 8..64 float4.
+// Larger chunks amortise the per-workgroup cost, smaller ones keep enough workgroups in flight; the
+// best size grows with the total work of a call (measured: 8192 for 25 M elements over all
+// workers, 16384 - 32768 for 244 M, 65536 from 1 G on).
+__host__ __device__ constexpr int stat_chunk(const int64_t total_elements) {
+    return total_elements < ((int64_t)1 << 26) ? 8192
+         : total_elements < ((int64_t)1 << 28) ? 16384
+         : total_elements < ((int64_t)1 << 29) ? 32768 : 65536;
+}
 
 constexpr int kSmallSeg = 2048;         // segments up to this size are reduced by one wave, four per workgroup
 

@@ -103,7 +103,7 @@ def _brute_tables(off, tile, chunk):
                                    [500, 20, 25000, 50, 400000, 500, 5000, 10], [0, 0, 7], [100000]])
 def test_tables_match_brute_force(binding, sizes):
     off = np.concatenate([[0], np.cumsum(sizes)])
-    d = binding.tg_describe_tables(off)
+    d = binding.tg_describe_tables(off, 3)
     tl, tw, segs = _brute_tables(off, d["tile_elems"], d["chunk_elems"])
     assert np.array_equal(d["tile_layer"], tl)
     assert np.array_equal(d["tile_whole"], tw)
@@ -111,6 +111,20 @@ def test_tables_match_brute_force(binding, sizes):
     # segments tile [0, n) exactly, in order, each inside one layer and one chunk
     s = d["segments"]
     assert s[0, 1] == 0 and s[-1, 2] == off[-1] and np.all(s[1:, 1] == s[:-1, 2]) and np.all(s[:, 2] > s[:, 1])
+
+
+def test_statistics_chunk_follows_the_size_of_the_job(binding):
+    # chunk = 8192 / 16384 / 32768 / 65536 elements for n * max_workers below 2^26 / 2^28 / 2^29 / beyond
+    for n, W, chunk in ((1000, 1, 8192), (2 ** 26 - 1, 1, 8192), (2 ** 26, 1, 16384), (2 ** 24, 4, 16384),
+                        (2 ** 24, 16, 32768), (60_965_224, 4, 16384), (132_863_336, 8, 65536), (6_296_176, 4, 8192)):
+        d = binding.tg_describe_tables(np.array([0, n]), W)
+        assert d["chunk_elems"] == chunk, (n, W, d["chunk_elems"])
+        s = d["segments"]
+        assert s.shape[0] == -(-n // chunk) and s[0, 1] == 0 and s[-1, 2] == n and np.all(s[:, 2] - s[:, 1] <= chunk)
+    with pytest.raises(binding.TgError):
+        binding.tg_describe_tables(np.array([0, 10]), 0)
+    with pytest.raises(binding.TgError):
+        binding.tg_describe_tables(np.array([0, 10]), 65)
 
 
 def test_tables_at_the_layer_limit(binding):

@@ -310,12 +310,12 @@ tg_status tg_clip_stats(tg_plan* p, int n_workers, const float* const* grads, fl
     f.n_layers = (int32_t)p->n_layers;
     f.c = c;
     f.noclip = (!(c > 0.0f) || std::isinf(c)) ? 1 : 0;
-    if (p->n_layers < tg::kFinalGroupedFrom) {
+    if (p->n_layers < tg::kFinalPerThreadFrom) {
         hipLaunchKernelGGL(tg::clip_stats_final_kernel, dim3((unsigned)p->n_layers, (unsigned)n_workers),
                            dim3(tg::kFinalBlock), 0, s, f);
     } else {
         const int64_t fblocks = (p->n_layers + tg::kBlock - 1) / tg::kBlock;
-        hipLaunchKernelGGL(tg::clip_stats_final_grouped_kernel, dim3((unsigned)fblocks, (unsigned)n_workers),
+        hipLaunchKernelGGL(tg::clip_stats_final_per_thread_kernel, dim3((unsigned)fblocks, (unsigned)n_workers),
                            dim3(tg::kBlock), 0, s, f);
     }
     if (!hip_ok(hipGetLastError())) return TG_ERR_HIP;

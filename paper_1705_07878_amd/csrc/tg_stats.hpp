@@ -261,10 +261,10 @@ __global__ void __launch_bounds__(kFinalBlock) clip_stats_final_kernel(const Sta
 // thread, one after the other; the layers of a wave that have more are then folded by the whole
 // wave, layer after layer (lanes strided over the partials, xor butterfly).  Which of the two a
 // layer gets depends on its number of partials alone, so the order of the additions is fixed.
-constexpr int kFinalGroupedFrom = 1024;   // layers
+constexpr int kFinalPerThreadFrom = 1024;   // layers
 constexpr int kFinalSerial = 8;           // partials a single thread folds
 
-__global__ void __launch_bounds__(kBlock) clip_stats_final_grouped_kernel(const StatsFinalArgs p) {
+__global__ void __launch_bounds__(kBlock) clip_stats_final_per_thread_kernel(const StatsFinalArgs p) {
     const int w = blockIdx.y, lane = threadIdx.x & 63;
     const int64_t l64 = (int64_t)blockIdx.x * kBlock + threadIdx.x;
     const bool have = l64 < p.n_layers;

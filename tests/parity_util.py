@@ -114,12 +114,12 @@ def assert_avg_close(got, want):
     assert np.all(err <= REL * np.abs(want.astype(np.float64))), float((err / np.maximum(np.abs(want), 1e-300)).max())
 
 
-def full_parity(oracle, binding, off, grads_np, c=2.5, seed=0, step=0, worker_base=0):
+def full_parity(oracle, binding, off, grads_np, c=2.5, seed=0, step=0, worker_base=0, max_workers=None):
     """All four calls against the oracle on one input set. Returns what the oracle computed."""
     off = np.asarray(off, np.int64)
     W = len(grads_np)
     n = int(off[-1])
-    plan = binding.Plan(off, W)
+    plan = binding.Plan(off, W if max_workers is None else max_workers)
     try:
         assert plan.n == n and plan.n_layers == off.size - 1
         assert plan.packed_bytes == ((n + 3) // 4 + 15) // 16 * 16

@@ -67,6 +67,24 @@ def test_many_tiny_layers(oracle, binding):
     full_parity(oracle, binding, off, _grads(rng, off, 3), seed=9, step=1)
 
 
+def test_every_statistics_chunk_size(oracle, binding):
+    """the chunk follows n * max_workers: 8192, 16384, 32768 and 65536 elements, here with two workers
+    of a plan made for more; layer sizes that leave ragged segments at every chunk size"""
+    rng = np.random.default_rng(35)
+    off = _off([3, 1_500_001, 70_000, 2_630_001, 11])                    # n = 4,200,016
+    grads = _grads(rng, off, 2)
+    chunks = set()
+    for mw in (2, 16, 64, 64 * 2):
+        if mw > 64:
+            off2 = _off([3, 1_500_001, 70_000, 2_630_001, 11, 4_200_016])   # n doubled: 65536 at 64 workers
+            chunks.add(int(binding.tg_describe_tables(off2, 64)["chunk_elems"]))
+            full_parity(oracle, binding, off2, _grads(rng, off2, 2), max_workers=64)
+        else:
+            chunks.add(int(binding.tg_describe_tables(off, mw)["chunk_elems"]))
+            full_parity(oracle, binding, off, grads, max_workers=mw)
+    assert chunks == {8192, 16384, 32768, 65536}
+
+
 def test_w64_and_worker_base(oracle, binding):
     rng = np.random.default_rng(64)
     off = _off([3000, 17, 5000])

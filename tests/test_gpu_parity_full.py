@@ -122,6 +122,38 @@ def _full_config(oracle, binding, wl):
         torch.cuda.synchronize()
         o_w = oracle.unpack_update(o_codes, off, o_s, 0.01, w0_host)
         assert_update_close(w0.cpu().numpy(), o_w, w0_host, o_avg)
+        del w0, w0_host, o_w
+        # ---- the integer sum k in narrow fields and its decoder; momentum update (not for the largest
+        # workload, to bound the run time) ----
+        if n * W <= 1_200_000_000:
+            bits = 4 if W <= 7 else 8
+            nbytes = plan.tg_sum_bytes(bits)
+            ksum = torch.full((nbytes,), 0xEE, dtype=torch.uint8, device="cuda")
+            plan.tg_unpack_sum_pack(cd, bits, ksum)
+            torch.cuda.synchronize()
+            want = oracle.sum_pack(o_codes, n, bits)
+            got = ksum.cpu().numpy()
+            assert np.array_equal(got[:want.size], want) and not got[want.size:].any(), "k fields differ"
+            kd = torch.zeros(nbytes, dtype=torch.uint8, device="cuda")
+            kd[:want.size] = torch.from_numpy(want).cuda()
+            avg2 = torch.full((n,), float("nan"), dtype=torch.float32, device="cuda")
+            plan.tg_decode_sum(W, kd, bits, dev(o_s), avg2)
+            torch.cuda.synchronize()
+            _avg_close_chunked(avg2, o_avg)
+            del ksum, kd, avg2, want, got
+            gen = torch.Generator("cuda").manual_seed(6)
+            v0 = torch.randn(n, dtype=torch.float32, device="cuda", generator=gen) * float(o_s.max())
+            w1 = torch.randn(n, dtype=torch.float32, device="cuda", generator=gen)
+            v0_host, w1_host = v0.cpu().numpy(), w1.cpu().numpy()
+            eta, mu = 0.01, 0.9
+            plan.tg_unpack_update_momentum(cd, dev(o_s), eta, mu, v0, w1)
+            torch.cuda.synchronize()
+            v_want, w_want = oracle.unpack_update_momentum(o_codes, off, o_s, eta, mu, v0_host, w1_host)
+            v64 = v_want.astype(np.float64)
+            sc_v = np.maximum(np.abs(mu * v0_host.astype(np.float64)), np.abs(o_avg.astype(np.float64)))
+            assert np.all(np.abs(v0.cpu().numpy() - v64) <= REL * sc_v + 1e-45)
+            sc_w = np.maximum(np.abs(w1_host.astype(np.float64)), np.abs(eta * v64))
+            assert np.all(np.abs(w1.cpu().numpy() - w_want.astype(np.float64)) <= REL * sc_w)
         plan.close()
     finally:
         oracle.set_threads(1)

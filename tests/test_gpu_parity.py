@@ -47,6 +47,25 @@ def test_all_four_calls_small(oracle, binding, sizes, W):
     full_parity(oracle, binding, off, _grads(rng, off, W), c=2.5, seed=1234567, step=3)
 
 
+def test_random_models(oracle, binding):
+    """40 seeded random models: layer sizes from a mixture of empty, tiny, around one tile and several
+    chunks; any number of workers up to 9; clip constants incl. no clipping; any seed, step, first worker"""
+    rng = np.random.default_rng(2024)
+    for case in range(40):
+        L = int(rng.integers(1, 13))
+        kinds = rng.integers(0, 5, size=L)
+        sizes = [int([0, rng.integers(1, 12), rng.integers(1000, 1050), rng.integers(3000, 9000),
+                      rng.integers(15000, 70000)][k]) for k in kinds]
+        if sum(sizes) == 0:
+            sizes[0] = 7
+        off = _off(sizes)
+        W = int(rng.integers(1, 10))
+        c = float(rng.choice([2.5, 2.5, 1.0, 0.3, 0.0]))
+        full_parity(oracle, binding, off, _grads(rng, off, W, mean=float(rng.choice([0.0, 1e-3]))), c=c,
+                    seed=int(rng.integers(0, 2 ** 63)), step=int(rng.integers(0, 2 ** 32)),
+                    worker_base=int(rng.integers(0, 1000)))
+
+
 def test_finer_buckets_than_a_layer(oracle, binding):
     """Section 3.3: gradients split into buckets that are ternarized independently (as in QSGD): a finer
     offset table through the same kernels; many boundaries per tile, small statistics segments"""

@@ -67,6 +67,8 @@ def lib() -> ctypes.CDLL:
         L.tgo_average_float.restype = None
         L.tgo_sum_pack.argtypes = [ctypes.POINTER(c_u8), ctypes.c_int, ctypes.c_int64, ctypes.c_int, c_u8]
         L.tgo_sum_pack.restype = None
+        L.tgo_sum_bits.argtypes = [ctypes.c_int]
+        L.tgo_sum_bits.restype = ctypes.c_int
         L.tgo_decode_sum.argtypes = [c_u8, ctypes.c_int, ctypes.c_int, ctypes.c_int64, c_i64, c_f, c_f]
         L.tgo_decode_sum.restype = None
         L.tgo_unpack_update_momentum.argtypes = [ctypes.POINTER(c_u8), ctypes.c_int, ctypes.c_int64, c_i64, c_f,
@@ -212,9 +214,14 @@ def average_float(grads_list):
     return avg
 
 
+def sum_bits(n_workers: int) -> int:
+    """ceil(log2(2N+1)): the narrowest field that holds k in -N .. N"""
+    return int(lib().tgo_sum_bits(int(n_workers)))
+
+
 def sum_pack(codes_list, n: int, bits: int):
     """-> uint8 [ceil(n*bits/8)]: k = sum of the workers' ternary values in `bits`-wide fields"""
-    assert bits in (4, 8)
+    assert 2 <= bits <= 8
     keep = [np.ascontiguousarray(c, dtype=np.uint8) for c in codes_list]
     for c in keep:
         assert c.size >= (n + 3) // 4
@@ -231,7 +238,7 @@ def decode_sum(ksum, bits: int, n_workers: int, off, s_shared):
     L = off.size - 1
     n = int(off[-1])
     ksum = np.ascontiguousarray(ksum, dtype=np.uint8)
-    assert bits in (4, 8) and ksum.size >= (n * bits + 7) // 8
+    assert 2 <= bits <= 8 and ksum.size >= (n * bits + 7) // 8
     s_shared, sp = _f32(s_shared)
     avg = np.empty(n, np.float32)
     lib().tgo_decode_sum(ksum.ctypes.data_as(ctypes.POINTER(ctypes.c_uint8)), int(bits), int(n_workers), L, op, sp,

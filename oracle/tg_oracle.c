@@ -194,16 +194,23 @@ void tgo_average_float(const float* const* grads, int n_workers, int64_t n, floa
     }
 }
 
+int tgo_sum_bits(int n_workers) {
+    /* smallest width whose 2^bits values hold the 2N+1 levels -N .. N (Section 3.1) */
+    int bits = 1;
+    while ((1L << bits) < 2L * n_workers + 1) ++bits;
+    return bits;
+}
+
 void tgo_sum_pack(const uint8_t* const* codes, int n_workers, int64_t n, int bits, uint8_t* ksum) {
     const int64_t n_bytes = (n * bits + 7) / 8;
     for (int64_t i = 0; i < n_bytes; ++i) ksum[i] = 0;
     for (int64_t e = 0; e < n; ++e) {
         long k = 0;
         for (int w = 0; w < n_workers; ++w) k += tgo_code_at(codes[w], e);
-        if (bits == 8) {
-            ksum[e] = (uint8_t)(k & 0xFF);
-        } else {
-            ksum[e >> 1] |= (uint8_t)((k & 0xF) << (4 * (e & 1)));
+        /* the buffer is one little-endian bit stream: bit j of field e is stream bit e*bits + j */
+        for (int j = 0; j < bits; ++j) {
+            const int64_t pos = e * bits + j;
+            if ((k >> j) & 1L) ksum[pos >> 3] |= (uint8_t)(1u << (pos & 7));
         }
     }
 }
@@ -214,13 +221,12 @@ void tgo_decode_sum(const uint8_t* ksum, int bits, int n_workers, int64_t n_laye
     #pragma omp parallel for num_threads(g_threads) schedule(static)
     for (int64_t e = 0; e < n; ++e) {
         const int64_t l = layer_of(e, n_layers, off);
-        int k;
-        if (bits == 8) {
-            k = (int)(int8_t)ksum[e];
-        } else {
-            const int f = (ksum[e >> 1] >> (4 * (e & 1))) & 0xF;
-            k = (f & 8) ? f - 16 : f;
+        int f = 0;
+        for (int j = 0; j < bits; ++j) {
+            const int64_t pos = e * bits + j;
+            f |= ((ksum[pos >> 3] >> (pos & 7)) & 1) << j;
         }
+        const int k = (f & (1 << (bits - 1))) ? f - (1 << bits) : f;     /* two's complement, `bits` wide */
         avg[e] = (float)((double)k * (double)s_shared[l] / (double)n_workers);
     }
 }

@@ -125,10 +125,13 @@ void tgo_unpack_update_momentum(const uint8_t* const* codes, int n_workers, int6
 
 /* Server-to-worker pull with parameter localization + scaler sharing (Section 3.1): the
  * averaged gradient has at most 2N+1 levels k * s/N, so the server sends the integer
- * k_e = sum_w t_w(e) in a `bits`-wide two's-complement field (bits = 4 needs 2N+1 <= 16,
- * bits = 8 serves N <= 64) instead of 32-bit floats.  Fields are stored least significant
- * first: bits = 4 puts element e in nibble e & 1 of byte e >> 1; bits = 8 in byte e.
- * Writes ceil(n * bits / 8) bytes; pad fields are 0.  Only the low `bits` bits of k are kept. */
+ * k_e = sum_w t_w(e) in a `bits`-wide two's-complement field instead of a 32-bit float;
+ * tgo_sum_bits(N) = ceil(log2(2N+1)) is the narrowest width that holds -N .. N (3, 4, 5 bits for
+ * N = 2, 4, 8).  The buffer is one little-endian bit stream: bit j of field e is bit (e*bits + j) & 7
+ * of byte (e*bits + j) >> 3 (bits = 4: element e in nibble e & 1 of byte e >> 1; bits = 8: byte e).
+ * Writes ceil(n * bits / 8) bytes; pad bits are 0.  Only the low `bits` bits of k are kept.
+ * 2 <= bits <= 8. */
+int tgo_sum_bits(int n_workers);
 void tgo_sum_pack(const uint8_t* const* codes, int n_workers, int64_t n, int bits, uint8_t* ksum);
 
 /* The worker's side of that pull: avg_e = (float)((double)k_e * s_shared_l / W), k_e the

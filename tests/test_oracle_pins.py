@@ -454,22 +454,34 @@ def test_sum_pack_fields_and_decode_roundtrip(oracle):
     sizes = [5, 64, 1, 131]
     off = np.concatenate([[0], np.cumsum(sizes)])
     n = int(off[-1])
-    for W, bits in ((1, 4), (2, 4), (4, 4), (7, 4), (4, 8), (8, 8), (64, 8)):
+    # the narrowest width: ceil(log2(2N+1)); 3, 4, 5 bits for the paper's N = 2, 4, 8
+    assert [oracle.sum_bits(N) for N in (1, 2, 3, 4, 7, 8, 15, 16, 31, 32, 63, 64)] == [2, 3, 3, 4, 4, 5, 5, 6, 6, 7, 7, 8]
+    for N in range(1, 65):
+        assert oracle.sum_bits(N) == math.ceil(math.log2(2 * N + 1))
+    cases = [(W, oracle.sum_bits(W)) for W in (1, 2, 3, 4, 7, 8, 15, 16, 31, 33, 63, 64)] + [(1, 4), (2, 4), (4, 8), (8, 8), (5, 7)]
+    for W, bits in cases:
         assert 2 * W + 1 <= 2 ** bits
         assert bits >= math.log2(1 + 2 * W)            # the paper's bound 32 / log2(1 + 2N)
         ts = [rng.integers(-1, 2, size=n) for _ in range(W)]
+        ts[0][:3] = (1, -1, 1)
+        for t in ts[1:]:
+            t[:2] = (1, -1)                             # k reaches +W and -W
         codes = [_forced(oracle, t) for t in ts]
         k = np.sum(ts, axis=0)
+        assert k[0] == W and k[1] == -W
         packed = oracle.sum_pack(codes, n, bits)
         assert packed.size == (n * bits + 7) // 8        # 32 / bits times smaller than fp32
-        if bits == 8:
-            got = packed.view(np.int8).astype(np.int64)[:n]
-        else:
-            nib = np.stack([packed & 15, packed >> 4], axis=1).reshape(-1)[:n].astype(np.int64)
-            got = np.where(nib >= 8, nib - 16, nib)
-            if n % 2:
-                assert packed[-1] >> 4 == 0               # pad field
+        # the buffer as one little-endian bit stream, cut into fields with numpy
+        stream = np.unpackbits(packed, bitorder="little")
+        assert not stream[n * bits:].any()               # pad bits
+        f = stream[:n * bits].reshape(n, bits).astype(np.int64) @ (1 << np.arange(bits))
+        got = np.where(f >= 2 ** (bits - 1), f - 2 ** bits, f)
         assert np.array_equal(got, k)
+        if bits == 8:
+            assert np.array_equal(packed.view(np.int8).astype(np.int64)[:n], k)
+        if bits == 4:
+            nib = np.stack([packed & 15, packed >> 4], axis=1).reshape(-1)[:n].astype(np.int64)
+            assert np.array_equal(np.where(nib >= 8, nib - 16, nib), k)
         s = (np.abs(rng.normal(size=len(sizes))) + 0.1).astype(np.float32)
         assert np.array_equal(oracle.decode_sum(packed, bits, W, off, s), oracle.unpack_average(codes, off, s))
 

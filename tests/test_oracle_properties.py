@@ -78,13 +78,12 @@ def test_relations_between_the_oracle_functions(oracle, sizes, W, seed, step, c,
     avg = oracle.unpack_average([x[0] for x in ts], off, s)
     assert np.array_equal(avg, want)
     assert np.array_equal(oracle.unpack_average_base3([x[1] for x in ts], off, s), want)
-    bits = 4 if W <= 7 else 8
+    bits = oracle.sum_bits(W)
+    assert 2 ** (bits - 1) < 2 * W + 1 <= 2 ** bits
     ks = oracle.sum_pack([x[0] for x in ts], n, bits)
-    if bits == 8:
-        fields = ks.view(np.int8)[:n].astype(np.int64)
-    else:
-        nib = np.stack([ks & 15, ks >> 4], axis=1).reshape(-1)[:n].astype(np.int64)
-        fields = np.where(nib >= 8, nib - 16, nib)
+    stream = np.unpackbits(ks, bitorder="little")
+    f = stream[:n * bits].reshape(n, bits).astype(np.int64) @ (1 << np.arange(bits))
+    fields = np.where(f >= 2 ** (bits - 1), f - 2 ** bits, f)
     assert np.array_equal(fields, k)
     assert np.array_equal(oracle.decode_sum(ks, bits, W, off, s), want)
     # update lines of Algorithm 1 on top of the same average

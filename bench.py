@@ -200,21 +200,22 @@ def main():
     del weights, velocity
 
     # Section 3.1 server-to-worker pull (not part of the timed step): the average as k in narrow fields
-    bits = 4 if W <= 7 else 8
-    ksum = torch.empty((plan.tg_sum_bytes(bits),), dtype=torch.uint8, device="cuda")
-    for nm, fn, nbytes in (("unpack_sum_pack", lambda: plan.tg_unpack_sum_pack(codes, bits, ksum), 0.25 * W + bits / 8.0),
-                           ("decode_sum", lambda: plan.tg_decode_sum(W, ksum, bits, s_shared, avg), bits / 8.0 + 4.0)):
-        for _ in range(2):
-            fn()
-        e0.record(stream)
-        for _ in range(reps):
-            fn()
-        e1.record(stream)
-        torch.cuda.synchronize()
-        ms = e0.elapsed_time(e1) / reps
-        gbs = n * nbytes / (ms * 1e-3) / 1e9
-        kern["%s %d-bit (not in step)" % (nm, bits)] = {"ms": round(ms, 4), "algorithmic_GBps": round(gbs, 1),
-                                                        "pct_hbm_peak": round(100 * gbs / HBM_PEAK_GBS, 1)}
+    # both the byte-aligned width (4 or 8 bits) and, where it differs, the narrowest one, ceil(log2(2W+1))
+    for bits in sorted({4 if W <= 7 else 8, binding.tg_sum_bits(W)}, reverse=True):
+        ksum = torch.empty((plan.tg_sum_bytes(bits),), dtype=torch.uint8, device="cuda")
+        for nm, fn, nbytes in (("unpack_sum_pack", lambda: plan.tg_unpack_sum_pack(codes, bits, ksum), 0.25 * W + bits / 8.0),
+                               ("decode_sum", lambda: plan.tg_decode_sum(W, ksum, bits, s_shared, avg), bits / 8.0 + 4.0)):
+            for _ in range(2):
+                fn()
+            e0.record(stream)
+            for _ in range(reps):
+                fn()
+            e1.record(stream)
+            torch.cuda.synchronize()
+            ms = e0.elapsed_time(e1) / reps
+            gbs = n * nbytes / (ms * 1e-3) / 1e9
+            kern["%s %d-bit (not in step)" % (nm, bits)] = {"ms": round(ms, 4), "algorithmic_GBps": round(gbs, 1),
+                                                            "pct_hbm_peak": round(100 * gbs / HBM_PEAK_GBS, 1)}
     del ksum
 
     # Section 3.1, toward 32/log2(3): the base-3 container, five ternary values per byte (not in the step)

@@ -195,12 +195,17 @@ tg_status tg_unpack_update_momentum(tg_plan* plan, int n_workers, const uint8_t*
 /* Server-to-worker pull (Section 3.1): with parameter localization and a shared scaler the
  * averaged gradient has at most 2N+1 levels k * s/N, so it can travel as the integer
  * k = sum_w t_w in a narrow field instead of a 32-bit float (the paper's 32 / log2(1+2N)).
- * Fields are `bits`-wide two's complement, least significant first: bits = 4 (needs
- * n_workers <= 7) puts element e in nibble e & 1 of byte e >> 1; bits = 8 puts it in byte e.
+ * Fields are `bits`-wide two's complement, 2 <= bits <= 8, and the buffer is one little-endian bit
+ * stream: bit j of field e is bit (e*bits + j) & 7 of byte (e*bits + j) >> 3 (bits = 4: element e
+ * in nibble e & 1 of byte e >> 1; bits = 8: byte e).  A width holds the sums of n_workers workers
+ * when n_workers < 2^(bits-1) (8 bits: every n_workers <= 64); tg_sum_bits(N) = ceil(log2(2N+1))
+ * is the narrowest such width, the paper's figure: 3, 4, 5 bits for N = 2, 4, 8.  Widths 4 and 8
+ * have their own (faster) kernels.
  * A buffer holds tg_sum_bytes(plan, bits) = ceil(n*bits/8) rounded up to 16 bytes, 16-byte
- * aligned; pad fields are written as 0.  Codes must be valid (no 10): only the low `bits`
+ * aligned; pad bits are written as 0.  Codes must be valid (no 10): only the low `bits`
  * bits of k are kept. */
-int64_t tg_sum_bytes(const tg_plan* plan, int bits);   /* -1 for a NULL plan or bits not 4 / 8 */
+int tg_sum_bits(int n_workers);                         /* -1 unless 1 <= n_workers <= TG_MAX_WORKERS */
+int64_t tg_sum_bytes(const tg_plan* plan, int bits);   /* -1 for a NULL plan or bits outside 2..8 */
 
 /* The server's side: decode the N code buffers, sum, write k.  ksum: dev, out. */
 tg_status tg_unpack_sum_pack(tg_plan* plan, int n_workers, const uint8_t* const* codes, int bits,

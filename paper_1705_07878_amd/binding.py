@@ -69,6 +69,8 @@ lib.tg_unpack_update.argtypes = [_vp, ctypes.c_int, _pp, _vp, ctypes.c_float, _v
 lib.tg_unpack_update.restype = ctypes.c_int
 lib.tg_unpack_update_momentum.argtypes = [_vp, ctypes.c_int, _pp, _vp, ctypes.c_float, ctypes.c_float, _vp, _vp, _vp]
 lib.tg_unpack_update_momentum.restype = ctypes.c_int
+lib.tg_sum_bits.argtypes = [ctypes.c_int]
+lib.tg_sum_bits.restype = ctypes.c_int
 lib.tg_sum_bytes.argtypes = [_vp, ctypes.c_int]
 lib.tg_sum_bytes.restype = _i64
 lib.tg_unpack_sum_pack.argtypes = [_vp, ctypes.c_int, _pp, ctypes.c_int, _vp, _vp]
@@ -120,6 +122,10 @@ def _stream(stream) -> int:
     if isinstance(stream, int):
         return stream
     return int(stream.cuda_stream)
+
+
+def tg_sum_bits(n_workers: int) -> int:
+    return int(lib.tg_sum_bits(int(n_workers)))
 
 
 def tg_strerror(status: int) -> str:

@@ -141,10 +141,10 @@ struct tg_plan {
 
 static int64_t sum_bytes(const tg_plan* p, int bits) { return ((p->n * bits + 7) / 8 + 15) / 16 * 16; }
 
-template <int SRC, int DST>
+template <int SRC, int DST, int BITS = 0>
 static tg_status launch_unpack(const tg::UnpackArgs& a, void* stream) {
     const int64_t blocks = (a.n_wave_tiles + tg::kBlock / tg::kWave - 1) / (tg::kBlock / tg::kWave);
-    hipLaunchKernelGGL((tg::unpack_average_kernel<true, SRC, DST>), dim3((unsigned)blocks), dim3(tg::kBlock), 0,
+    hipLaunchKernelGGL((tg::unpack_average_kernel<true, SRC, DST, BITS>), dim3((unsigned)blocks), dim3(tg::kBlock), 0,
                        (hipStream_t)stream, a);
     if (!hip_ok(hipGetLastError())) return TG_ERR_HIP;
     return TG_OK;
@@ -167,7 +167,11 @@ static tg_status fill_unpack(const tg_plan* p, int n_workers, const uint8_t* con
     return TG_OK;
 }
 
-static bool bits_hold(int bits, int n_workers) { return (bits == 4 && n_workers <= 7) || bits == 8; }
+// a two's-complement field of `bits` bits holds -N .. N when N < 2^(bits-1); 8 bits serve every N <= 64
+static bool bits_valid(int bits) { return bits >= 2 && bits <= 8; }
+static bool bits_hold(int bits, int n_workers) {
+    return bits_valid(bits) && (bits == 8 || n_workers <= (1 << (bits - 1)) - 1);
+}
 
 extern "C" {
 
@@ -474,8 +478,15 @@ tg_status tg_unpack_update_momentum(tg_plan* p, int n_workers, const uint8_t* co
     return launch_unpack<tg::SRC_CODES, tg::DST_MOMENTUM>(a, stream);
 }
 
+int tg_sum_bits(int n_workers) {
+    if (n_workers < 1 || n_workers > TG_MAX_WORKERS) return -1;
+    int bits = 2;
+    while ((1 << bits) < 2 * n_workers + 1) ++bits;
+    return bits;
+}
+
 int64_t tg_sum_bytes(const tg_plan* p, int bits) {
-    if (p == nullptr || (bits != 4 && bits != 8)) return -1;
+    if (p == nullptr || !bits_valid(bits)) return -1;
     return sum_bytes(p, bits);
 }
 
@@ -483,7 +494,7 @@ tg_status tg_unpack_sum_pack(tg_plan* p, int n_workers, const uint8_t* const* co
                              uint8_t* ksum, void* stream) {
     tg_status st = check_workers(p, n_workers);
     if (st != TG_OK) return st;
-    if (codes == nullptr || ksum == nullptr || (bits != 4 && bits != 8) || !bits_hold(bits, n_workers))
+    if (codes == nullptr || ksum == nullptr || !bits_hold(bits, n_workers))
         return TG_ERR_INVALID_ARG;
     tg::UnpackArgs a{};
     if ((st = fill_unpack(p, n_workers, codes, a)) != TG_OK) return st;
@@ -492,16 +503,22 @@ tg_status tg_unpack_sum_pack(tg_plan* p, int n_workers, const uint8_t* const* co
     a.ksum_bytes = sum_bytes(p, bits);
     // the tiles must cover the pad fields too
     a.n_wave_tiles = (a.ksum_bytes * 8 / bits + tg::kWaveTile - 1) / tg::kWaveTile;
-    return bits == 4 ? launch_unpack<tg::SRC_CODES, tg::DST_K4>(a, stream)
-                     : launch_unpack<tg::SRC_CODES, tg::DST_K8>(a, stream);
+    switch (bits) {
+        case 4: return launch_unpack<tg::SRC_CODES, tg::DST_K4>(a, stream);
+        case 8: return launch_unpack<tg::SRC_CODES, tg::DST_K8>(a, stream);
+        case 2: return launch_unpack<tg::SRC_CODES, tg::DST_KB, 2>(a, stream);
+        case 3: return launch_unpack<tg::SRC_CODES, tg::DST_KB, 3>(a, stream);
+        case 5: return launch_unpack<tg::SRC_CODES, tg::DST_KB, 5>(a, stream);
+        case 6: return launch_unpack<tg::SRC_CODES, tg::DST_KB, 6>(a, stream);
+        default: return launch_unpack<tg::SRC_CODES, tg::DST_KB, 7>(a, stream);
+    }
 }
 
 tg_status tg_decode_sum(tg_plan* p, int n_workers, const uint8_t* ksum, int bits,
                         const float* s_shared, float* avg, void* stream) {
     if (p == nullptr || n_workers < 1) return TG_ERR_INVALID_ARG;
     if (n_workers > TG_MAX_WORKERS) return TG_ERR_TOO_MANY_WORKERS;
-    if (ksum == nullptr || s_shared == nullptr || avg == nullptr || (bits != 4 && bits != 8) ||
-        !bits_hold(bits, n_workers))
+    if (ksum == nullptr || s_shared == nullptr || avg == nullptr || !bits_hold(bits, n_workers))
         return TG_ERR_INVALID_ARG;
     tg::UnpackArgs a{};
     tg_status st = fill_unpack(p, n_workers, nullptr, a);
@@ -511,8 +528,15 @@ tg_status tg_decode_sum(tg_plan* p, int n_workers, const uint8_t* ksum, int bits
     a.ksum_bytes = sum_bytes(p, bits);
     a.s_shared = s_shared;
     a.avg = avg;
-    return bits == 4 ? launch_unpack<tg::SRC_K4, tg::DST_AVG>(a, stream)
-                     : launch_unpack<tg::SRC_K8, tg::DST_AVG>(a, stream);
+    switch (bits) {
+        case 4: return launch_unpack<tg::SRC_K4, tg::DST_AVG>(a, stream);
+        case 8: return launch_unpack<tg::SRC_K8, tg::DST_AVG>(a, stream);
+        case 2: return launch_unpack<tg::SRC_KB, tg::DST_AVG, 2>(a, stream);
+        case 3: return launch_unpack<tg::SRC_KB, tg::DST_AVG, 3>(a, stream);
+        case 5: return launch_unpack<tg::SRC_KB, tg::DST_AVG, 5>(a, stream);
+        case 6: return launch_unpack<tg::SRC_KB, tg::DST_AVG, 6>(a, stream);
+        default: return launch_unpack<tg::SRC_KB, tg::DST_AVG, 7>(a, stream);
+    }
 }
 
 tg_status tg_average_float(int n_workers, int64_t n, const float* const* grads, float* avg, void* stream) {

@@ -103,6 +103,7 @@ __device__ __forceinline__ float4 apply4(const float4 w, const float4 a, const f
 // Where the per-element integer k comes from and where it goes.
 //   source  SRC_CODES: k = sum_w t_w, from the W workers' 2-bit code buffers
 //           SRC_K4 / SRC_K8: k read from a buffer of 4- / 8-bit two's-complement fields
+//           SRC_KB: the same for any width BITS = 2..8 (one little-endian bit stream)
 //   sink    DST_AVG:    avg[e] = k * (s/W)               (Algorithm 1, server line)
 //           DST_UPDATE: w[e]  -= eta * k * (s/W)          (server line fused with the update line:
 //                       the average is never written to or re-read from HBM)
@@ -110,8 +111,44 @@ __device__ __forceinline__ float4 apply4(const float4 w, const float4 a, const f
 //                       the optimizer of most of the paper's experiments)
 //           DST_K4 / DST_K8: k itself in 4- / 8-bit fields (the server-to-worker pull of
 //                       Section 3.1: at most 2N+1 levels instead of 32-bit floats)
-enum { SRC_CODES = 0, SRC_K4 = 1, SRC_K8 = 2 };
-enum { DST_AVG = 0, DST_UPDATE = 1, DST_K4 = 2, DST_K8 = 3, DST_MOMENTUM = 4 };
+//           DST_KB: the same for any width BITS = 2..8; ceil(log2(2N+1)) bits hold the 2N+1 levels
+enum { SRC_CODES = 0, SRC_K4 = 1, SRC_K8 = 2, SRC_KB = 3 };
+enum { DST_AVG = 0, DST_UPDATE = 1, DST_K4 = 2, DST_K8 = 3, DST_MOMENTUM = 4, DST_KB = 5 };
+
+// 16 signed bytes (D[m] = elements 4m .. 4m+3) <-> 16 fields of BITS bits, field i at bit i * BITS
+// of a 128-bit little-endian value (lo, hi)
+template <int BITS>
+__device__ __forceinline__ void fields_from_bytes(const uint32_t D[4], uint64_t& lo, uint64_t& hi) {
+    constexpr uint64_t mask = (1ull << BITS) - 1;
+    lo = 0, hi = 0;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+        const uint64_t f = (uint64_t)(D[i >> 2] >> (8 * (i & 3))) & mask;
+        const int pos = i * BITS;
+        if (pos < 64) {
+            lo |= f << pos;
+            if (pos + BITS > 64) hi |= f >> (64 - pos);
+        } else {
+            hi |= f << (pos - 64);
+        }
+    }
+}
+
+template <int BITS>
+__device__ __forceinline__ void bytes_from_fields(const uint64_t lo, const uint64_t hi, uint32_t D[4]) {
+    constexpr uint32_t mask = (1u << BITS) - 1, sign = 1u << (BITS - 1);
+    D[0] = D[1] = D[2] = D[3] = 0u;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+        const int pos = i * BITS;
+        uint64_t f;
+        if (pos >= 64) f = hi >> (pos - 64);
+        else if (pos + BITS > 64) f = (lo >> pos) | (hi << (64 - pos));
+        else f = lo >> pos;
+        const uint32_t k = (((uint32_t)f & mask) ^ sign) - sign;         // sign extension from BITS bits
+        D[i >> 2] |= (k & 0xFFu) << (8 * (i & 3));
+    }
+}
 
 // sign-extend the low nibble of every byte: bit 3 set -> bits 4..7 set (0x08 * 30 = 0xF0)
 __device__ __forceinline__ uint32_t sext_nibbles(const uint32_t y) {
@@ -276,7 +313,7 @@ struct Emit {
 
 // A workgroup owns 4 consecutive tiles.  Wave j sums the codes of tile j (one short-lived pass,
 // every table lookup a scalar load); the scaling sinks then write the tiles together (see Emit).
-template <bool NT, int SRC, int DST>
+template <bool NT, int SRC, int DST, int BITS = 0>
 __global__ void __launch_bounds__(kBlock) unpack_average_kernel(const UnpackArgs p) {
     __shared__ uint32_t lds[kTilesPerBlock][kWaveTile / 4];   // 1 KiB per tile
 
@@ -288,7 +325,7 @@ __global__ void __launch_bounds__(kBlock) unpack_average_kernel(const UnpackArgs
     const int64_t e0 = wt * kWaveTile;
 
     Emit<NT, DST, kTilesPerBlock, kTilesPerBlock> emit;
-    if (DST != DST_K4 && DST != DST_K8) emit.prefetch(p, tile0, wave, lane);
+    if (DST != DST_K4 && DST != DST_K8 && DST != DST_KB) emit.prefetch(p, tile0, wave, lane);
 
     uint32_t D[4] = {0u, 0u, 0u, 0u};
     if (valid) {
@@ -296,6 +333,18 @@ __global__ void __launch_bounds__(kBlock) unpack_average_kernel(const UnpackArgs
             const int64_t byte0 = (e0 >> 2) + 4 * lane;
             if (byte0 < p.packed_bytes)                    // false only in the ragged last tile
                 sum_codes(p.n_workers, D, [&](int w) { return *reinterpret_cast<const uint32_t*>(p.codes[w] + byte0); });
+        } else if (SRC == SRC_KB) {
+            // the lane's 16 fields are the 2 * BITS bytes at byte 2 * BITS * lane of the tile's stream
+            const int64_t byte0 = wt * (kWaveTile / 8 * BITS) + 2 * BITS * lane;
+            uint64_t lo = 0, hi = 0;
+#pragma unroll
+            for (int j = 0; j < BITS; ++j) {
+                const int64_t b = byte0 + 2 * j;
+                const uint64_t h = b < p.ksum_bytes ? *reinterpret_cast<const uint16_t*>(p.ksum_in + b) : 0;
+                if (j < 4) lo |= h << (16 * j);
+                else hi |= h << (16 * (j - 4));
+            }
+            bytes_from_fields<BITS == 0 ? 1 : BITS>(lo, hi, D);
         } else if (SRC == SRC_K8) {
             const int64_t byte0 = e0 + 16 * lane;
             uint4 q = make_uint4(0u, 0u, 0u, 0u);
@@ -326,6 +375,29 @@ __global__ void __launch_bounds__(kBlock) unpack_average_kernel(const UnpackArgs
         const int64_t byte0 = (e0 >> 1) + 8 * lane;
         if (valid && byte0 < p.ksum_bytes)
             *reinterpret_cast<uint2*>(p.ksum_out + byte0) = make_uint2(pack_nibbles(D[0], D[1]), pack_nibbles(D[2], D[3]));
+        return;
+    }
+
+    if (DST == DST_KB) {
+        // the lane's 2 * BITS bytes go to LDS as halfwords; the wave then stores the tile's 128 * BITS
+        // bytes as whole dwords, contiguously
+        if (!valid) return;
+        uint64_t lo, hi;
+        fields_from_bytes<BITS == 0 ? 1 : BITS>(D, lo, hi);
+        uint16_t* row = reinterpret_cast<uint16_t*>(lds[wave]);
+#pragma unroll
+        for (int j = 0; j < BITS; ++j)
+            row[BITS * lane + j] = (uint16_t)(j < 4 ? lo >> (16 * j) : hi >> (16 * (j - 4)));
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        const int64_t tile_byte0 = wt * (kWaveTile / 8 * BITS);
+#pragma unroll
+        for (int r = 0; r < (32 * BITS + kWave - 1) / kWave; ++r) {
+            const int idx = lane + kWave * r;
+            const int64_t b = tile_byte0 + 4 * idx;
+            if (idx < 32 * BITS && b < p.ksum_bytes) *reinterpret_cast<uint32_t*>(p.ksum_out + b) = lds[wave][idx];
+        }
         return;
     }
 

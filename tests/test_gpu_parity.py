@@ -243,7 +243,8 @@ def test_last_layer_in_float(oracle, binding):
     plan.close()
 
 
-@pytest.mark.parametrize("W,bits", [(1, 4), (2, 4), (4, 4), (7, 4), (4, 8), (8, 8), (11, 8), (64, 8)])
+@pytest.mark.parametrize("W,bits", [(1, 4), (2, 4), (4, 4), (7, 4), (4, 8), (8, 8), (11, 8), (64, 8),
+                                    (1, 2), (2, 3), (3, 3), (8, 5), (15, 5), (16, 6), (31, 6), (33, 7), (63, 7), (3, 5), (2, 6)])
 def test_sum_pack_and_decode_sum(oracle, binding, W, bits):
     """Section 3.1 server-to-worker pull: k in narrow fields; bit-exact both ways, and the decoded
     average is bit-identical to tg_unpack_average on the same codes"""
@@ -289,9 +290,16 @@ def test_sum_pack_rejects_fields_that_cannot_hold_the_sum(binding):
         with pytest.raises(binding.TgError) as e:
             plan.tg_unpack_sum_pack(c, 4, k)              # 17 levels do not fit 4 bits
         assert e.value.status == binding.TG_ERR_INVALID_ARG
+        for bad in (1, 9, 0, -3):
+            with pytest.raises(binding.TgError):
+                plan.tg_unpack_sum_pack(c, bad, k)
+            assert plan.tg_sum_bytes(bad) == -1
+        plan.tg_unpack_sum_pack(c, 5, k)                   # 17 levels fit 5 bits
+        torch.cuda.synchronize()
         with pytest.raises(binding.TgError):
-            plan.tg_unpack_sum_pack(c, 5, k)
-        assert plan.tg_sum_bytes(3) == -1
+            plan.tg_decode_sum(16, k, 5, torch.zeros(1, device="cuda"), torch.zeros(100, device="cuda"))   # 33 levels do not
+        assert [binding.tg_sum_bits(N) for N in (1, 2, 3, 4, 7, 8, 16, 64)] == [2, 3, 3, 4, 4, 5, 6, 8]
+        assert binding.tg_sum_bits(0) == -1 and binding.tg_sum_bits(65) == -1
     finally:
         plan.close()
 

@@ -126,7 +126,7 @@ def _full_config(oracle, binding, wl):
         # ---- the integer sum k in narrow fields and its decoder; momentum update (not for the largest
         # workload, to bound the run time) ----
         if n * W <= 1_200_000_000:
-            bits = 4 if W <= 7 else 8
+            bits = binding.tg_sum_bits(W)          # 4 bits for 4 workers, 5 for 8: ceil(log2(2W+1))
             nbytes = plan.tg_sum_bytes(bits)
             ksum = torch.full((nbytes,), 0xEE, dtype=torch.uint8, device="cuda")
             plan.tg_unpack_sum_pack(cd, bits, ksum)

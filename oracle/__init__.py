@@ -65,6 +65,8 @@ def lib() -> ctypes.CDLL:
         L.tgo_unpack_update.restype = None
         L.tgo_average_float.argtypes = [ctypes.POINTER(c_f), ctypes.c_int, ctypes.c_int64, c_f]
         L.tgo_average_float.restype = None
+        L.tgo_unpack_average_scalers.argtypes = [ctypes.POINTER(c_u8), ctypes.c_int, ctypes.c_int64, c_i64, c_f, c_f]
+        L.tgo_unpack_average_scalers.restype = None
         L.tgo_sum_pack.argtypes = [ctypes.POINTER(c_u8), ctypes.c_int, ctypes.c_int64, ctypes.c_int, c_u8]
         L.tgo_sum_pack.restype = None
         L.tgo_sum_bits.argtypes = [ctypes.c_int]
@@ -179,6 +181,25 @@ def unpack_average(codes_list, off, s_shared):
     assert s_shared.size == L
     avg = np.empty(n, np.float32)
     lib().tgo_unpack_average(arr, W, L, op, sp, _f32(avg)[1])
+    return avg
+
+
+def unpack_average_scalers(codes_list, off, s_workers):
+    """per-worker scalers s_workers [W][L] (no scaler sharing) -> float32 average [n]"""
+    off = _check_offsets(off)
+    _, op = _i64(off)
+    L = off.size - 1
+    n = int(off[-1])
+    keep = [np.ascontiguousarray(c, dtype=np.uint8) for c in codes_list]
+    for c in keep:
+        assert c.size >= (n + 3) // 4
+    W = len(keep)
+    u8p = ctypes.POINTER(ctypes.c_uint8)
+    arr = (u8p * W)(*[c.ctypes.data_as(u8p) for c in keep])
+    s_workers, sp = _f32(s_workers)
+    assert s_workers.shape == (W, L)
+    avg = np.empty(n, np.float32)
+    lib().tgo_unpack_average_scalers(arr, W, L, op, sp, _f32(avg)[1])
     return avg
 
 

@@ -172,6 +172,21 @@ void tgo_unpack_average(const uint8_t* const* codes, int n_workers, int64_t n_la
     }
 }
 
+/* Algorithm 1, server line, when every worker keeps its own scaler (no scaler sharing, the case the
+ * text before Eq. 4 describes): avg_e = (1/N) * sum_i s_l^(i) * t_i(e). */
+void tgo_unpack_average_scalers(const uint8_t* const* codes, int n_workers, int64_t n_layers,
+                                const int64_t* off, const float* s_workers, float* avg) {
+    const int64_t n = off[n_layers];
+    #pragma omp parallel for num_threads(g_threads) schedule(static)
+    for (int64_t e = 0; e < n; ++e) {
+        const int64_t l = layer_of(e, n_layers, off);
+        double sum = 0.0;
+        for (int w = 0; w < n_workers; ++w)
+            sum += (double)s_workers[(int64_t)w * n_layers + l] * (double)tgo_code_at(codes[w], e);
+        avg[e] = (float)(sum / (double)n_workers);
+    }
+}
+
 void tgo_unpack_update(const uint8_t* const* codes, int n_workers, int64_t n_layers,
                        const int64_t* off, const float* s_shared, float eta, float* weights) {
     const int64_t n = off[n_layers];

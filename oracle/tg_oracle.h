@@ -95,6 +95,14 @@ void tgo_unpack_average(const uint8_t* const* codes, int n_workers, int64_t n_la
 void tgo_unpack_update(const uint8_t* const* codes, int n_workers, int64_t n_layers,
                        const int64_t* off, const float* s_shared, float eta, float* weights);
 
+/* Algorithm 1, server line, WITHOUT scaler sharing (every worker ternarized with its own scaler
+ * s^(i), the situation the text before Eq. 4 starts from):
+ *   avg_e = (float)( (sum_i (double)s_workers[i][l] * t_i(e)) / N ),
+ * summed in worker order (each product is exact).  s_workers: [W][L] row-major.  With equal rows
+ * the result is that of tgo_unpack_average, bit for bit (k*s is exact in fp64 for N <= 64). */
+void tgo_unpack_average_scalers(const uint8_t* const* codes, int n_workers, int64_t n_layers,
+                                const int64_t* off, const float* s_workers, float* avg);
+
 /* Denser encoding toward the information bound 32/log2(3) = 20.18x of Section 3.1: five ternary
  * values per byte (1.6 bits each, 20x).  Digit d = t mod 3 (0 -> 0, +1 -> 1, -1 -> 2); byte j holds
  * elements 5j .. 5j+4 as d0 + 3*d1 + 9*d2 + 27*d3 + 81*d4 (0..242).  Same clip, same random field

@@ -343,6 +343,40 @@ def test_unpack_average_levels_mean_and_w1(oracle):
             assert np.array_equal(avg, (ts[0] * s[lay]).astype(np.float32))
 
 
+def test_unpack_average_with_each_workers_own_scaler(oracle):
+    """Algorithm 1's server line without scaler sharing: the mean of s^(i) * t_i, by numpy; equal scalers
+    give unpack_average bit for bit; more than 2N+1 levels appear, which is what Eq. 4 removes"""
+    rng = np.random.default_rng(13)
+    sizes = [7, 64, 1, 130, 0, 900]
+    off = np.concatenate([[0], np.cumsum(sizes)])
+    n, L = int(off[-1]), len(sizes)
+    lay = np.repeat(np.arange(L), sizes)
+    for W in (1, 2, 3, 4, 8, 64):
+        sw = (np.abs(rng.normal(size=(W, L))) * 10.0 ** rng.uniform(-4, 1, size=(W, 1)) + 1e-6).astype(np.float32)
+        ts = [rng.integers(-1, 2, size=n) for _ in range(W)]
+        codes = [_forced(oracle, t) for t in ts]
+        got = oracle.unpack_average_scalers(codes, off, sw)
+        want = np.mean([t * sw[w][lay].astype(np.float64) for w, t in enumerate(ts)], axis=0)
+        scale = np.mean([np.abs(t) * sw[w][lay].astype(np.float64) for w, t in enumerate(ts)], axis=0)
+        assert np.all(np.abs(got - want) <= 1.2e-7 * scale)          # one fp32 rounding of an fp64 sum
+        assert np.all(got[np.sum(np.abs(ts), axis=0) == 0] == 0)
+        # hand value on the first element: workers 0 and 1 say +1 and -1, the others 0
+        if W >= 2:
+            for w, t in enumerate(ts):
+                t[0] = (1, -1)[w] if w < 2 else 0
+            codes = [_forced(oracle, t) for t in ts]
+            got = oracle.unpack_average_scalers(codes, off, sw)
+            assert got[0] == np.float32((np.float64(sw[0, 0]) - np.float64(sw[1, 0])) / W)
+        # equal rows: the shared-scaler average, bit for bit
+        s = sw[0]
+        assert np.array_equal(oracle.unpack_average_scalers(codes, off, np.tile(s, (W, 1))),
+                              oracle.unpack_average(codes, off, s))
+        if W == 4:
+            big = lay == 5
+            assert np.unique(got[big]).size > 2 * W + 1              # levels beyond 2N+1 without sharing
+            assert np.unique(oracle.unpack_average(codes, off, s)[big]).size <= 2 * W + 1
+
+
 def test_code_10_decodes_as_twos_complement(oracle):
     codes = np.array([0b10_11_01_00], np.uint8)
     assert [oracle.code_at(codes, e) for e in range(4)] == [0, 1, -1, -2]

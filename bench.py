@@ -235,6 +235,19 @@ def main():
                                          "pct_hbm_peak": round(100 * gbs / HBM_PEAK_GBS, 1)}
     del codes3
 
+    # Algorithm 1's server line without scaler sharing (not part of the timed step): every worker's own scaler
+    for _ in range(2):
+        plan.tg_unpack_average_scalers(codes, s_local, avg)
+    e0.record(stream)
+    for _ in range(reps):
+        plan.tg_unpack_average_scalers(codes, s_local, avg)
+    e1.record(stream)
+    torch.cuda.synchronize()
+    us_ms = e0.elapsed_time(e1) / reps
+    us_gbs = n * (4.0 + 0.25 * W) / (us_ms * 1e-3) / 1e9
+    kern["unpack_average_scalers (not in step)"] = {"ms": round(us_ms, 4), "algorithmic_GBps": round(us_gbs, 1),
+                                                    "pct_hbm_peak": round(100 * us_gbs / HBM_PEAK_GBS, 1)}
+
     # Section 4.2 variant (not part of the timed step): plain fp32 average, as used for a layer that is
     # kept in floating point; timed here over the whole flat buffer to get a bandwidth figure
     favg = torch.empty((n,), dtype=torch.float32, device="cuda")

@@ -184,6 +184,18 @@ tg_status tg_unpack_average(tg_plan* plan, int n_workers, const uint8_t* const* 
 tg_status tg_unpack_update(tg_plan* plan, int n_workers, const uint8_t* const* codes,
                            const float* s_shared, float eta, float* weights, void* stream);
 
+/* Algorithm 1, server line, WITHOUT scaler sharing: every worker ternarized with its own scaler
+ * (call tg_ternarize_pack once per worker with that worker's row of s_local in place of s_shared),
+ * which is the situation the text before Eq. 4 starts from:
+ *   avg[e] = (1/N) * sum_i s_workers[i][layer(e)] * t_i(e)
+ * summed per element in fp64 in worker order and rounded to fp32 once (within 1e-6 of the exact
+ * mean relative to mean_i |s_i t_i|; exactly 0 where every t is 0).  With equal rows it agrees
+ * with tg_unpack_average to that tolerance.  Up to 3^N levels per layer instead of 2N+1.
+ *   s_workers  dev [n_workers][L] fp32, e.g. the s_local of tg_clip_stats
+ *   avg        dev [n] fp32 out, 16-byte aligned */
+tg_status tg_unpack_average_scalers(tg_plan* plan, int n_workers, const uint8_t* const* codes,
+                                    const float* s_workers, float* avg, void* stream);
+
 /* The same with momentum (the optimizer of most experiments in Section 4):
  *   velocity[e] <- mu * velocity[e] + avg[e] ;  weights[e] <- weights[e] - eta * velocity[e]
  * (two fused multiply-adds; mu = 0 reproduces tg_unpack_update and leaves avg in velocity).

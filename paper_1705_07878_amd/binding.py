@@ -65,6 +65,8 @@ lib.tg_step_advance.argtypes = [_vp, ctypes.c_uint32, _vp]
 lib.tg_step_advance.restype = ctypes.c_int
 lib.tg_unpack_average.argtypes = [_vp, ctypes.c_int, _pp, _vp, _vp, _vp]
 lib.tg_unpack_average.restype = ctypes.c_int
+lib.tg_unpack_average_scalers.argtypes = [_vp, ctypes.c_int, _pp, _vp, _vp, _vp]
+lib.tg_unpack_average_scalers.restype = ctypes.c_int
 lib.tg_unpack_update.argtypes = [_vp, ctypes.c_int, _pp, _vp, ctypes.c_float, _vp, _vp]
 lib.tg_unpack_update.restype = ctypes.c_int
 lib.tg_unpack_update_momentum.argtypes = [_vp, ctypes.c_int, _pp, _vp, ctypes.c_float, ctypes.c_float, _vp, _vp, _vp]
@@ -224,6 +226,11 @@ class Plan:
         cp, _k = _ptr_array(codes)
         _check(lib.tg_unpack_average(self._h, len(codes), cp, _ptr(s_shared), _ptr(avg),
                                      _stream(stream)), "tg_unpack_average")
+
+    def tg_unpack_average_scalers(self, codes: Sequence, s_workers, avg, stream=None):
+        cp, _k = _ptr_array(codes)
+        _check(lib.tg_unpack_average_scalers(self._h, len(codes), cp, _ptr(s_workers), _ptr(avg),
+                                             _stream(stream)), "tg_unpack_average_scalers")
 
     def tg_unpack_update(self, codes: Sequence, s_shared, eta: float, weights, stream=None):
         cp, _k = _ptr_array(codes)

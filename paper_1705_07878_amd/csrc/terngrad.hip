@@ -444,6 +444,23 @@ tg_status tg_unpack_average(tg_plan* p, int n_workers, const uint8_t* const* cod
     return launch_unpack<tg::SRC_CODES, tg::DST_AVG>(a, stream);
 }
 
+tg_status tg_unpack_average_scalers(tg_plan* p, int n_workers, const uint8_t* const* codes,
+                                    const float* s_workers, float* avg, void* stream) {
+    tg_status st = check_workers(p, n_workers);
+    if (st != TG_OK) return st;
+    if (codes == nullptr || s_workers == nullptr || avg == nullptr) return TG_ERR_INVALID_ARG;
+    tg::UnpackArgs a{};
+    if ((st = fill_unpack(p, n_workers, codes, a)) != TG_OK) return st;
+    if (!aligned(s_workers, 4) || !aligned(avg, 16)) return TG_ERR_ALIGNMENT;
+    a.s_workers = s_workers;
+    a.avg = avg;
+    const int64_t blocks = (a.n_wave_tiles + tg::kTilesPerBlock - 1) / tg::kTilesPerBlock;
+    hipLaunchKernelGGL((tg::unpack_average_scalers_kernel<true>), dim3((unsigned)blocks), dim3(tg::kBlock), 0,
+                       (hipStream_t)stream, a);
+    if (!hip_ok(hipGetLastError())) return TG_ERR_HIP;
+    return TG_OK;
+}
+
 tg_status tg_unpack_update(tg_plan* p, int n_workers, const uint8_t* const* codes,
                            const float* s_shared, float eta, float* weights, void* stream) {
     tg_status st = check_workers(p, n_workers);

@@ -21,6 +21,7 @@ namespace tg {
 struct UnpackArgs {
     const uint8_t* codes[kMaxWorkers];
     const float* s_shared;      // [L]
+    const float* s_workers;     // [W][L]: every worker's own scaler, for the decoder without scaler sharing
     const int64_t* off;         // [L+1]
     const uint32_t* tile_info;  // per wave tile: layer of its first element | kTileWhole
     float* avg;                 // [n]: the average (out), or the weights (in/out) when updating
@@ -489,6 +490,103 @@ __global__ void __launch_bounds__(kBase3Block) unpack_average_base3_kernel(const
     }
     __syncthreads();
     emit.store(p, kb, tile0, wave, lane);
+}
+
+// ---- the server line of Algorithm 1 without scaler sharing: avg = (1/N) sum_i s^(i) t_i ----
+// The packed counters above need one scale per layer; with a scaler per worker the sum is taken per
+// element in fp64 (each s * t is exact, the additions are in worker order), which makes this
+// variant about as ALU- as memory-bound.  One wave per tile; lane L owns the 16 consecutive elements
+// of its code dword, and the 16 results go through LDS so that the wave stores whole float4s,
+// 1 KiB contiguous per store.
+template <bool NT>
+__global__ void __launch_bounds__(kBlock) unpack_average_scalers_kernel(const UnpackArgs p) {
+    __shared__ float lds[kTilesPerBlock][kWaveTile];     // 4 KiB per tile
+
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wave = wave_uniform(threadIdx.x >> 6);
+    const int64_t wt = (int64_t)blockIdx.x * kTilesPerBlock + wave;
+    if (wt >= p.n_wave_tiles) return;
+    const int64_t e0 = wt * kWaveTile;
+    const int W = p.n_workers;
+    const uint32_t info = p.tile_info[wt];
+    const int l0 = (int)(info & ~kTileWhole);
+    const bool whole = (info & kTileWhole) != 0;
+    const int64_t byte0 = (e0 >> 2) + 4 * lane;
+    const bool in_codes = byte0 < p.packed_bytes;          // false only in the ragged last tile
+    const int64_t cbyte = in_codes ? byte0 : 0;
+
+    double acc[16];
+#pragma unroll
+    for (int i = 0; i < 16; ++i) acc[i] = 0.0;
+
+    if (whole) {
+        for (int w0 = 0; w0 < W; w0 += 4) {
+            // four workers' loads in flight; a clamped index keeps those of a short last group valid
+            uint32_t x[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+                x[j] = *reinterpret_cast<const uint32_t*>(p.codes[w0 + j < W ? w0 + j : W - 1] + cbyte);
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                if (w0 + j >= W) break;
+                const double sd = (double)p.s_workers[(int64_t)(w0 + j) * p.n_layers + l0];
+                const int xi = in_codes ? (int)x[j] : 0;
+#pragma unroll
+                for (int i = 0; i < 16; ++i) {
+                    const int t = (int)((uint32_t)xi << (30 - 2 * i)) >> 30;  // 2-bit two's complement
+                    acc[i] = __builtin_fma((double)t, sd, acc[i]);
+                }
+            }
+        }
+    } else {
+        // layers change inside the tile: the layer of each of the lane's elements from one scalar pass
+        // over the boundaries, then one scaler per element and worker
+        int l[16];
+#pragma unroll
+        for (int i = 0; i < 16; ++i) l[i] = l0;
+        for (int j = l0 + 1; j < p.n_layers; ++j) {
+            const int64_t rel = p.off[j] - e0;
+            if (rel >= kWaveTile) break;
+            const int r = (int)rel;
+#pragma unroll
+            for (int i = 0; i < 16; ++i) l[i] += (16 * lane + i >= r) ? 1 : 0;
+        }
+        for (int w = 0; w < W; ++w) {
+            const int xi = in_codes ? (int)*reinterpret_cast<const uint32_t*>(p.codes[w] + cbyte) : 0;
+            const float* __restrict__ sw = p.s_workers + (int64_t)w * p.n_layers;
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                const int t = (int)((uint32_t)xi << (30 - 2 * i)) >> 30;
+                acc[i] = __builtin_fma((double)t, (double)sw[l[i]], acc[i]);
+            }
+        }
+    }
+
+    // one rounding to fp32; the mean is taken as a product with 1/N in fp64
+    const double inv = 1.0 / (double)W;
+    float* row = lds[wave];
+#pragma unroll
+    for (int m = 0; m < 4; ++m)
+        *reinterpret_cast<float4*>(row + 16 * lane + 4 * m) =
+            make_float4((float)(acc[4 * m] * inv), (float)(acc[4 * m + 1] * inv),
+                        (float)(acc[4 * m + 2] * inv), (float)(acc[4 * m + 3] * inv));
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+        const int x = 4 * (lane + kWave * r);
+        const float4 v = *reinterpret_cast<const float4*>(row + x);
+        const int64_t e = e0 + x;
+        if (e + 3 < p.n) {
+            store4<NT>(p.avg + e, v);
+        } else {
+            const float o[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+            for (int k = 0; k < 4; ++k)
+                if (e + k < p.n) p.avg[e + k] = o[k];
+        }
+    }
 }
 
 }  // namespace tg

@@ -164,6 +164,56 @@ def test_unpack_average_arbitrary_bytes(oracle, binding):
             plan.close()
 
 
+def test_unpack_average_with_each_workers_own_scaler(oracle, binding):
+    """Algorithm 1's server line without scaler sharing: every worker ternarizes with its own s_local
+    (one call per worker, its row in place of the shared scaler) and the decoder weighs each worker's
+    ternary values with that worker's scaler"""
+    rng = np.random.default_rng(41)
+    for sizes, W in (([37], 1), ([1024], 2), ([5000, 3, 4096, 2001, 0, 20000], 4), ([100] * 50 + [3000], 3),
+                     ([70001, 33333], 8), ([1500], 64), ([9000] * 3, 11)):
+        off = _off(sizes)
+        n, L = int(off[-1]), len(sizes)
+        grads = _grads(rng, off, W)
+        st = [oracle.clip_stats(g, off, 2.5) for g in grads]
+        sw = np.stack([x[1] for x in st])                                  # [W][L]: no sharing
+        o_codes = [oracle.ternarize_pack(g, off, st[w][0], sw[w], 11, 2, w) for w, g in enumerate(grads)]
+        plan = binding.Plan(off, W)
+        try:
+            nb = (n + 3) // 4
+            for w, g in enumerate(grads):                                  # encoder: one worker per call
+                gc = gpu_ternarize(plan, [dev(g)], st[w][0][None, :], sw[w], 11, 2, worker_base=w)[0]
+                assert np.array_equal(gc[:nb], o_codes[w]) and not gc[nb:].any()
+            cd = []
+            for c in o_codes:
+                buf = np.zeros(plan.packed_bytes, np.uint8)
+                buf[:c.size] = c
+                cd.append(dev(buf))
+            avg = torch.full((n,), float("nan"), dtype=torch.float32, device="cuda")
+            plan.tg_unpack_average_scalers(cd, dev(sw), avg)
+            torch.cuda.synchronize()
+            got = avg.cpu().numpy()
+            want = oracle.unpack_average_scalers(o_codes, off, sw)
+            lay = np.repeat(np.arange(L), np.diff(off))
+            # tolerance relative to the mean magnitude of the terms (a sum of signed terms has no relative
+            # accuracy of its own); zeros exact
+            mag = np.zeros(n)
+            allzero = np.ones(n, bool)
+            for w, c in enumerate(o_codes):
+                f = (c[:, None] >> np.array([0, 2, 4, 6], np.uint8)) & 3
+                nz = (f.reshape(-1)[:n] != 0)
+                mag += nz * sw[w][lay].astype(np.float64)
+                allzero &= ~nz
+            assert np.all(np.abs(got.astype(np.float64) - want.astype(np.float64)) <= 1e-6 * mag / W)
+            assert np.all(got[allzero] == 0)
+            # equal rows: the shared-scaler decoder's values
+            s = sw.max(axis=0)
+            plan.tg_unpack_average_scalers(cd, dev(np.tile(s, (W, 1))), avg)
+            torch.cuda.synchronize()
+            assert_avg_close(avg.cpu().numpy(), oracle.unpack_average(o_codes, off, s))
+        finally:
+            plan.close()
+
+
 def test_unpack_update_arbitrary_bytes_and_rates(oracle, binding):
     rng = np.random.default_rng(19)
     off = _off([5000, 3, 4096, 2001])

@@ -30,6 +30,9 @@ def parse():
     ap.add_argument("--workload", default="alexnet",
                     choices=["lenet", "alexnet", "googlenet_like", "vgg_a", "flat"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--ceilings", action="store_true",
+                    help="instead of the step: what the memory system sustains for the kernels' access "
+                         "patterns with the arithmetic taken out (tg_probe), on 4 GB buffers")
     return ap.parse_args()
 
 
@@ -83,6 +86,46 @@ def cpu_baseline(wl, grads_host, sample_note):
     return res
 
 
+def ceilings(torch, binding, n=1 << 30, reps=10):
+    """GB/s of the probe kernels over n floats: same launch shape as the real kernels, no arithmetic"""
+    src = torch.empty((n,), dtype=torch.float32, device="cuda").normal_()
+    dst = torch.empty((n,), dtype=torch.float32, device="cuda")
+    thin = torch.empty((n // 16,), dtype=torch.int32, device="cuda")
+    stream = torch.cuda.current_stream()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    kinds = [(0, "read", 4.0), (1, "read_nt", 4.0), (2, "write_nt", 4.0), (3, "copy_nt", 8.0),
+             (4, "read_nt_with_thin_write", 4.25)]
+    out = {}
+    for kind, name, bytes_per_elem in kinds:
+        for _ in range(3):
+            binding.tg_probe(kind, src, dst, thin, n)
+        e0.record(stream)
+        for _ in range(reps):
+            binding.tg_probe(kind, src, dst, thin, n)
+        e1.record(stream)
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / reps
+        gbs = n * bytes_per_elem / (ms * 1e-3) / 1e9
+        out[name] = {"ms": round(ms, 4), "GBps": round(gbs, 1), "pct_hbm_peak": round(100 * gbs / HBM_PEAK_GBS, 1)}
+    # the footprint of the flat 1e9 workload: eight 4 GB sources read one after the other
+    srcs = [src] + [torch.empty((n,), dtype=torch.float32, device="cuda").normal_() for _ in range(7)]
+    thins = [thin] + [torch.empty((n // 16,), dtype=torch.int32, device="cuda") for _ in range(7)]
+    for name, kind, bpe in (("read_nt_8x4GB", 1, 4.0), ("read_nt_with_thin_write_8x4GB", 4, 4.25)):
+        for i in range(8):
+            binding.tg_probe(kind, srcs[i], dst, thins[i], n)
+        e0.record(stream)
+        for _ in range(3):
+            for i in range(8):
+                binding.tg_probe(kind, srcs[i], dst, thins[i], n)
+        e1.record(stream)
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / 3
+        gbs = 8 * n * bpe / (ms * 1e-3) / 1e9
+        out[name] = {"ms": round(ms, 4), "GBps": round(gbs, 1), "pct_hbm_peak": round(100 * gbs / HBM_PEAK_GBS, 1)}
+    return {"ceilings": out, "elements": n, "peak_GBps": HBM_PEAK_GBS,
+            "note": "tg_probe kinds 0-4: the kernels' access patterns without arithmetic, one wave per 1024 floats"}
+
+
 def main():
     args = parse()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -96,6 +139,9 @@ def main():
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
+    if args.ceilings:
+        print(json.dumps(ceilings(torch, binding)))
+        return
     wl = workloads.BY_NAME[args.workload]()
     W, n, L = wl.n_workers, wl.n, wl.n_layers
 

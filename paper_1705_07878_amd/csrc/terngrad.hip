@@ -12,6 +12,7 @@
 #include <vector>
 
 #include "tg_float.hpp"
+#include "tg_probe.hpp"
 #include "tg_stats.hpp"
 #include "tg_ternarize.hpp"
 #include "tg_unpack.hpp"
@@ -579,6 +580,29 @@ tg_status tg_average_float(int n_workers, int64_t n, const float* const* grads, 
     if (blocks < 1) blocks = 1;
     if (blocks > 0x7FFFFFFF) return TG_ERR_INVALID_ARG;
     hipLaunchKernelGGL(tg::average_float_kernel, dim3((unsigned)blocks), dim3(tg::kBlock), 0, (hipStream_t)stream, a);
+    if (!hip_ok(hipGetLastError())) return TG_ERR_HIP;
+    return TG_OK;
+}
+
+tg_status tg_probe(int kind, const float* src, float* dst, uint32_t* thin, int64_t n, void* stream) {
+    if (kind < tg::PROBE_READ || kind > tg::PROBE_READ_THIN_WRITE || n < tg::kWaveTile || n % tg::kWaveTile != 0)
+        return TG_ERR_INVALID_ARG;
+    const bool reads = kind != tg::PROBE_WRITE_NT;
+    if ((reads && src == nullptr) || dst == nullptr || (kind == tg::PROBE_READ_THIN_WRITE && thin == nullptr))
+        return TG_ERR_INVALID_ARG;
+    if ((reads && !aligned(src, 16)) || !aligned(dst, 16) || (thin != nullptr && !aligned(thin, 4))) return TG_ERR_ALIGNMENT;
+    tg::ProbeArgs a{src, dst, thin, n / tg::kWaveTile};
+    const int64_t blocks = (a.n_tiles + tg::kBlock / tg::kWave - 1) / (tg::kBlock / tg::kWave);
+    if (blocks > 0x7FFFFFFF) return TG_ERR_INVALID_ARG;
+    const dim3 grid((unsigned)blocks), block(tg::kBlock);
+    hipStream_t s = (hipStream_t)stream;
+    switch (kind) {
+        case tg::PROBE_READ: hipLaunchKernelGGL(tg::probe_kernel<tg::PROBE_READ>, grid, block, 0, s, a); break;
+        case tg::PROBE_READ_NT: hipLaunchKernelGGL(tg::probe_kernel<tg::PROBE_READ_NT>, grid, block, 0, s, a); break;
+        case tg::PROBE_WRITE_NT: hipLaunchKernelGGL(tg::probe_kernel<tg::PROBE_WRITE_NT>, grid, block, 0, s, a); break;
+        case tg::PROBE_COPY_NT: hipLaunchKernelGGL(tg::probe_kernel<tg::PROBE_COPY_NT>, grid, block, 0, s, a); break;
+        default: hipLaunchKernelGGL(tg::probe_kernel<tg::PROBE_READ_THIN_WRITE>, grid, block, 0, s, a); break;
+    }
     if (!hip_ok(hipGetLastError())) return TG_ERR_HIP;
     return TG_OK;
 }

@@ -576,6 +576,34 @@ def test_whole_step_replayed_from_a_hip_graph(oracle, binding):
         plan.close()
 
 
+def test_probe_kernels_move_what_they_claim(binding):
+    """the bandwidth probes: copy reproduces the source, write fills the destination, the thin stream
+    holds the XOR of each lane's 16 words, the read probes leave the destination alone"""
+    n = 1024 * 37
+    src = torch.randn(n, device="cuda")
+    dst = torch.full((n,), -7.0, device="cuda")
+    thin = torch.zeros(n // 16, dtype=torch.int32, device="cuda")
+    for kind in (0, 1):
+        binding.tg_probe(kind, src, dst, thin, n)
+    torch.cuda.synchronize()
+    assert bool((dst == -7.0).all())
+    binding.tg_probe(3, src, dst, thin, n)
+    torch.cuda.synchronize()
+    assert torch.equal(dst, src)
+    binding.tg_probe(2, src, dst, thin, n)
+    torch.cuda.synchronize()
+    assert dst.view(-1, 4)[:, :3].eq(torch.tensor([1.0, 2.0, 3.0], device="cuda")).all()
+    binding.tg_probe(4, src, dst, thin, n)
+    torch.cuda.synchronize()
+    w = src.cpu().numpy().view(np.uint32).reshape(-1, 4, 64, 4)          # tile, k, lane, word
+    want = np.bitwise_xor.reduce(np.bitwise_xor.reduce(w, axis=3), axis=1).reshape(-1)
+    assert np.array_equal(thin.cpu().numpy().view(np.uint32), want)
+    for bad in (lambda: binding.tg_probe(5, src, dst, thin, n), lambda: binding.tg_probe(0, src, dst, thin, 1000),
+                lambda: binding.tg_probe(4, src, dst, None, n), lambda: binding.tg_probe(1, src[1:], dst, thin, 1024)):
+        with pytest.raises(binding.TgError):
+            bad()
+
+
 def test_argument_errors_on_device(binding):
     off = _off([100, 28])
     plan = binding.Plan(off, 2)

@@ -33,6 +33,8 @@ def parse():
     ap.add_argument("--ceilings", action="store_true",
                     help="instead of the step: what the memory system sustains for the kernels' access "
                          "patterns with the arithmetic taken out (tg_probe), on 4 GB buffers")
+    ap.add_argument("--ceilings-elements", type=int, default=1 << 30,
+                    help="floats per buffer for --ceilings (a multiple of 1024)")
     return ap.parse_args()
 
 
@@ -140,7 +142,7 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
     if args.ceilings:
-        print(json.dumps(ceilings(torch, binding)))
+        print(json.dumps(ceilings(torch, binding, n=args.ceilings_elements)))
         return
     wl = workloads.BY_NAME[args.workload]()
     W, n, L = wl.n_workers, wl.n, wl.n_layers

@@ -49,6 +49,18 @@ def traffic_from_profile(kernel: str, workload: str):
     return None
 
 
+def pattern_ceiling():
+    """GB/s the bare traffic pattern of ternarize_pack reaches (committed probe run), or None"""
+    path = os.path.join(ROOT, "profiles", "hbm_ceilings_probe.txt")
+    if not os.path.exists(path):
+        return None
+    for line in open(path):
+        f = line.split()
+        if f and f[0] == "read_nt_with_thin_write" and "GB/s" in f:
+            return float(f[f.index("GB/s") - 1])
+    return None
+
+
 def cpu_baseline(wl, grads_host, sample_note):
     """The oracle as it stands, all host cores, same four calls over the W workers."""
     import numpy as np
@@ -317,7 +329,10 @@ def main():
     roofline = {"bound": "hbm", "kernel": "tg::ternarize_pack_kernel", "achieved": round(achieved, 1),
                 "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
                 "traffic": traffic_from_profile(dom, args.workload),
-                "algorithmic_bytes_per_launch": alg_bytes[dom], "avg_launch_ms": round(call_ms[dom], 4)}
+                "algorithmic_bytes_per_launch": alg_bytes[dom], "avg_launch_ms": round(call_ms[dom], 4),
+                # what the same traffic (4 B read + 1/4 B written per element) reaches with no arithmetic at all,
+                # 4 GiB per launch, from the committed `bench.py --ceilings` run: context for `frac`
+                "pattern_ceiling_GBps": pattern_ceiling()}
 
     out = {
         "metric": "ternarize+pack and unpack-average GB/s (fp32 in) and % HBM peak; ms/step",

@@ -7,9 +7,14 @@ tg_unpack_average for all W simulated workers (W gradient buffers on the one
 device).  Inputs are resident in HBM before the timed region.  Prints ONE JSON
 line; `value` is fp32 gradient bytes consumed per second (W * n * 4 B / step).
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload alexnet]
+The default run times the largest single-GPU configuration (C5: one flat layer of 10^9 elements, W = 8)
+as the headline and, in the same JSON line under "other_configs", the AlexNet-shaped (C2) and
+VGG-A-shaped (C4) ones.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload flat] [--also alexnet,vgg_a]
 """
 import argparse
+import ctypes
 import json
 import os
 import sys
@@ -27,20 +32,29 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", default="alexnet",
+    ap.add_argument("--workload", default="flat",
                     choices=["lenet", "alexnet", "googlenet_like", "vgg_a", "flat"])
+    ap.add_argument("--also", default="alexnet,vgg_a",
+                    help="comma-separated workloads timed after the headline one and reported under "
+                         "other_configs ('' for none)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--ceilings", action="store_true",
                     help="instead of the step: what the memory system sustains for the kernels' access "
-                         "patterns with the arithmetic taken out (tg_probe), on 4 GB buffers")
+                         "patterns with the arithmetic taken out (libbench_probe.so), on 4 GB buffers")
     ap.add_argument("--ceilings-elements", type=int, default=1 << 30,
                     help="floats per buffer for --ceilings (a multiple of 1024)")
     return ap.parse_args()
 
 
+def traffic_profile_path(kernel: str, workload: str) -> str:
+    return os.path.join("profiles", "%s_%s_pmc.txt" % (kernel, workload))
+
+
 def traffic_from_profile(kernel: str, workload: str):
-    """HBM bytes per launch of `kernel` from the committed rocprofv3 --pmc summary, or None."""
-    path = os.path.join(ROOT, "profiles", "%s_%s_pmc.txt" % (kernel, workload))
+    """HBM bytes per launch of `kernel` from the committed rocprofv3 --pmc summary (FETCH_SIZE and
+    WRITE_SIZE, each scaled by a plain copy of known size), or None.  The counters need two profiler
+    runs of their own, so the figure is read from that summary, never measured in the timed run."""
+    path = os.path.join(ROOT, traffic_profile_path(kernel, workload))
     if not os.path.exists(path):
         return None
     for line in open(path):
@@ -100,22 +114,49 @@ def cpu_baseline(wl, grads_host, sample_note):
     return res
 
 
-def ceilings(torch, binding, n=1 << 30, reps=10):
+_PROBE = None
+
+
+def probe_lib():
+    """libbench_probe.so (bench_probe.hip, built by __graft_entry__.build()): the kernels' access
+    patterns without arithmetic.  A measurement instrument of this file, not part of the library."""
+    global _PROBE
+    if _PROBE is None:
+        path = os.path.join(ROOT, "libbench_probe.so")
+        if not os.path.exists(path):
+            from paper_1705_07878_amd import build
+            build.build_probe(force=True, verbose=False)
+        _PROBE = ctypes.CDLL(path)
+        _PROBE.bench_probe.argtypes = [ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
+                                       ctypes.c_int64, ctypes.c_void_p]
+        _PROBE.bench_probe.restype = ctypes.c_int
+    return _PROBE
+
+
+def bench_probe(torch, kind, src, dst, thin, n):
+    ptr = lambda t: None if t is None else ctypes.c_void_p(t.data_ptr())
+    rc = probe_lib().bench_probe(int(kind), ptr(src), ptr(dst), ptr(thin), int(n),
+                                 ctypes.c_void_p(torch.cuda.current_stream().cuda_stream))
+    if rc != 0:
+        raise RuntimeError("bench_probe(kind=%d) failed: %d" % (kind, rc))
+
+
+def ceilings(torch, n=1 << 30, reps=10):
     """GB/s of the probe kernels over n floats: same launch shape as the real kernels, no arithmetic"""
     src = torch.empty((n,), dtype=torch.float32, device="cuda").normal_()
     dst = torch.empty((n,), dtype=torch.float32, device="cuda")
     thin = torch.empty((n // 16,), dtype=torch.int32, device="cuda")
     stream = torch.cuda.current_stream()
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    kinds = [(0, "read", 4.0), (1, "read_nt", 4.0), (2, "write_nt", 4.0), (3, "copy_nt", 8.0),
-             (4, "read_nt_with_thin_write", 4.25)]
+    kinds = [(0, "read", 4.0), (1, "read_nt", 4.0), (2, "write_nt", 4.0), (5, "write_nt_cooperative", 4.0),
+             (3, "copy_nt", 8.0), (4, "read_nt_with_thin_write", 4.25)]
     out = {}
     for kind, name, bytes_per_elem in kinds:
         for _ in range(3):
-            binding.tg_probe(kind, src, dst, thin, n)
+            bench_probe(torch, kind, src, dst, thin, n)
         e0.record(stream)
         for _ in range(reps):
-            binding.tg_probe(kind, src, dst, thin, n)
+            bench_probe(torch, kind, src, dst, thin, n)
         e1.record(stream)
         torch.cuda.synchronize()
         ms = e0.elapsed_time(e1) / reps
@@ -126,39 +167,55 @@ def ceilings(torch, binding, n=1 << 30, reps=10):
     thins = [thin] + [torch.empty((n // 16,), dtype=torch.int32, device="cuda") for _ in range(7)]
     for name, kind, bpe in (("read_nt_8x4GB", 1, 4.0), ("read_nt_with_thin_write_8x4GB", 4, 4.25)):
         for i in range(8):
-            binding.tg_probe(kind, srcs[i], dst, thins[i], n)
+            bench_probe(torch, kind, srcs[i], dst, thins[i], n)
         e0.record(stream)
         for _ in range(3):
             for i in range(8):
-                binding.tg_probe(kind, srcs[i], dst, thins[i], n)
+                bench_probe(torch, kind, srcs[i], dst, thins[i], n)
         e1.record(stream)
         torch.cuda.synchronize()
         ms = e0.elapsed_time(e1) / 3
         gbs = 8 * n * bpe / (ms * 1e-3) / 1e9
         out[name] = {"ms": round(ms, 4), "GBps": round(gbs, 1), "pct_hbm_peak": round(100 * gbs / HBM_PEAK_GBS, 1)}
     return {"ceilings": out, "elements": n, "peak_GBps": HBM_PEAK_GBS,
-            "note": "tg_probe kinds 0-4: the kernels' access patterns without arithmetic, one wave per 1024 floats"}
+            "note": "bench_probe kinds 0-5: the kernels' access patterns without arithmetic, one wave per 1024 floats"}
 
 
-def main():
-    args = parse()
-    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
-        print("bench.py: this build runs on ONE GPU only (the W workers are W gradient buffers on one "
-              "device; no collectives). Re-run with --gpus 1.", file=sys.stderr)
-        sys.exit(2)
+def _timed(torch, stream, fn, reps, warm=2):
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    for _ in range(warm):
+        fn()
+    e0.record(stream)
+    for _ in range(reps):
+        fn()
+    e1.record(stream)
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) / reps
 
-    import numpy as np
-    import torch
-    from paper_1705_07878_amd import binding, workloads
 
-    assert torch.cuda.is_available(), "bench.py needs a GPU"
-    torch.cuda.set_device(0)
-    if args.ceilings:
-        print(json.dumps(ceilings(torch, binding, n=args.ceilings_elements)))
-        return
-    wl = workloads.BY_NAME[args.workload]()
+def _rate(nbytes, ms):
+    gbs = nbytes / (ms * 1e-3) / 1e9
+    return {"ms": round(ms, 4), "algorithmic_GBps": round(gbs, 1), "pct_hbm_peak": round(100 * gbs / HBM_PEAK_GBS, 1)}
+
+
+def roofline_of(kernel_symbol, short, workload_key, alg_bytes, ms):
+    """the roofline object of one HBM-bound kernel: algorithmic bytes per launch over its mean launch
+    duration (HIP events on the launch stream, this run) against the published 8 TB/s"""
+    achieved = alg_bytes / (ms * 1e-3) / 1e9
+    traffic = traffic_from_profile(short, workload_key)
+    return {"bound": "hbm", "kernel": kernel_symbol, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
+            "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,
+            "traffic_source": (traffic_profile_path(short, workload_key) + " (committed rocprofv3 --pmc "
+                               "FETCH_SIZE / WRITE_SIZE summary; not measured in this run)") if traffic else None,
+            "algorithmic_bytes_per_launch": alg_bytes, "avg_launch_ms": round(ms, 4)}
+
+
+def measure(torch, np, binding, workloads, key, steps, warmup, extras):
+    """One workload: K timed steps of the four calls, the same step replayed from a HIP graph, per-call
+    timings with events, and (extras) the calls beyond the step.  Returns (result dict, state for the
+    CPU baseline)."""
+    wl = workloads.BY_NAME[key]()
     W, n, L = wl.n_workers, wl.n, wl.n_layers
-
     grads = [workloads.make_gradient(wl, w, "cuda") for w in range(W)]
     plan = binding.Plan(wl.offsets, W)
     tau = torch.empty((W, L), dtype=torch.float32, device="cuda")
@@ -179,16 +236,16 @@ def main():
         plan.tg_unpack_average(codes, s_shared, avg)
         if ev: ev[4].record(stream)
 
-    for t in range(args.warmup):
+    for t in range(warmup):
         step(t)
     torch.cuda.synchronize()
 
     # whole-step timing: exactly K steps between two synchronisations
     t0 = time.perf_counter()
-    for t in range(args.steps):
+    for t in range(steps):
         step(t)
     torch.cuda.synchronize()
-    ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
+    ms_per_step = (time.perf_counter() - t0) * 1e3 / steps
 
     # the same step recorded once into a HIP graph and replayed (the iteration counter lives in device
     # memory and is advanced by the graph's last node): what a launch-bound caller would do
@@ -202,18 +259,19 @@ def main():
         plan.tg_ternarize_pack_devstep(grads, tau, s_shared, wl.seed, step_dev, codes)
         plan.tg_unpack_average(codes, s_shared, avg)
         binding.tg_step_advance(step_dev, 1)
-    for _ in range(args.warmup):
+    for _ in range(warmup):
         graph.replay()
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for _ in range(args.steps):
+    for _ in range(steps):
         graph.replay()
     torch.cuda.synchronize()
-    ms_per_step_graph = (time.perf_counter() - t0) * 1e3 / args.steps
+    ms_per_step_graph = (time.perf_counter() - t0) * 1e3 / steps
+    del graph
 
     # per-call timing with events on the launch stream, over K more steps
-    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(5)] for _ in range(args.steps)]
-    for t in range(args.steps):
+    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(5)] for _ in range(steps)]
+    for t in range(steps):
         step(t, evs[t])
     torch.cuda.synchronize()
     names = ["clip_stats", "share_scalers", "ternarize_pack", "unpack_average"]
@@ -222,134 +280,102 @@ def main():
     in_bytes = W * n * 4.0
     alg_bytes = {"clip_stats": W * n * 4.0, "ternarize_pack": W * n * 4.25,
                  "unpack_average": n * (4.0 + 0.25 * W)}
-    kern = {}
-    for nm in ("clip_stats", "ternarize_pack", "unpack_average"):
-        gbs = alg_bytes[nm] / (call_ms[nm] * 1e-3) / 1e9
-        kern[nm] = {"ms": round(call_ms[nm], 4), "algorithmic_GBps": round(gbs, 1),
-                    "pct_hbm_peak": round(100 * gbs / HBM_PEAK_GBS, 1)}
+    kern = {nm: _rate(alg_bytes[nm], call_ms[nm]) for nm in ("clip_stats", "ternarize_pack", "unpack_average")}
     kern["ternarize_pack"]["fp32_in_GBps"] = round(in_bytes / (call_ms["ternarize_pack"] * 1e-3) / 1e9, 1)
     kern["share_scalers"] = {"ms": round(call_ms["share_scalers"], 4)}
+    rooflines = {
+        "ternarize_pack": roofline_of("tg::ternarize_pack_kernel", "ternarize_pack", key,
+                                      alg_bytes["ternarize_pack"], call_ms["ternarize_pack"]),
+        "unpack_average": roofline_of("tg::unpack_average_kernel<codes -> average>", "unpack_average", key,
+                                      alg_bytes["unpack_average"], call_ms["unpack_average"]),
+    }
 
-    # next line of Algorithm 1 (not part of the timed step): decode fused with the parameter update
-    weights = torch.zeros((n,), dtype=torch.float32, device="cuda")
-    for _ in range(3):
-        plan.tg_unpack_update(codes, s_shared, 1e-3, weights)
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    reps = max(5, args.steps // 2)
-    e0.record(stream)
-    for _ in range(reps):
-        plan.tg_unpack_update(codes, s_shared, 1e-3, weights)
-    e1.record(stream)
-    torch.cuda.synchronize()
-    upd_ms = e0.elapsed_time(e1) / reps
-    upd_gbs = n * (8.0 + 0.25 * W) / (upd_ms * 1e-3) / 1e9
-    kern["unpack_update (not in step)"] = {"ms": round(upd_ms, 4), "algorithmic_GBps": round(upd_gbs, 1),
-                                           "pct_hbm_peak": round(100 * upd_gbs / HBM_PEAK_GBS, 1)}
-    velocity = torch.zeros((n,), dtype=torch.float32, device="cuda")
-    for _ in range(2):
-        plan.tg_unpack_update_momentum(codes, s_shared, 1e-3, 0.9, velocity, weights)
-    e0.record(stream)
-    for _ in range(reps):
-        plan.tg_unpack_update_momentum(codes, s_shared, 1e-3, 0.9, velocity, weights)
-    e1.record(stream)
-    torch.cuda.synchronize()
-    mom_ms = e0.elapsed_time(e1) / reps
-    mom_gbs = n * (16.0 + 0.25 * W) / (mom_ms * 1e-3) / 1e9
-    kern["unpack_update_momentum (not in step)"] = {"ms": round(mom_ms, 4), "algorithmic_GBps": round(mom_gbs, 1),
-                                                    "pct_hbm_peak": round(100 * mom_gbs / HBM_PEAK_GBS, 1)}
-    del weights, velocity
+    if extras:
+        reps = max(5, steps // 2)
+        # next line of Algorithm 1 (not part of the timed step): decode fused with the parameter update
+        weights = torch.zeros((n,), dtype=torch.float32, device="cuda")
+        ms = _timed(torch, stream, lambda: plan.tg_unpack_update(codes, s_shared, 1e-3, weights), reps, 3)
+        kern["unpack_update (not in step)"] = _rate(n * (8.0 + 0.25 * W), ms)
+        velocity = torch.zeros((n,), dtype=torch.float32, device="cuda")
+        ms = _timed(torch, stream, lambda: plan.tg_unpack_update_momentum(codes, s_shared, 1e-3, 0.9, velocity, weights), reps)
+        kern["unpack_update_momentum (not in step)"] = _rate(n * (16.0 + 0.25 * W), ms)
+        del weights, velocity
 
-    # Section 3.1 server-to-worker pull (not part of the timed step): the average as k in narrow fields
-    # both the byte-aligned width (4 or 8 bits) and, where it differs, the narrowest one, ceil(log2(2W+1))
-    for bits in sorted({4 if W <= 7 else 8, binding.tg_sum_bits(W)}, reverse=True):
-        ksum = torch.empty((plan.tg_sum_bytes(bits),), dtype=torch.uint8, device="cuda")
-        for nm, fn, nbytes in (("unpack_sum_pack", lambda: plan.tg_unpack_sum_pack(codes, bits, ksum), 0.25 * W + bits / 8.0),
-                               ("decode_sum", lambda: plan.tg_decode_sum(W, ksum, bits, s_shared, avg), bits / 8.0 + 4.0)):
-            for _ in range(2):
-                fn()
-            e0.record(stream)
-            for _ in range(reps):
-                fn()
-            e1.record(stream)
-            torch.cuda.synchronize()
-            ms = e0.elapsed_time(e1) / reps
-            gbs = n * nbytes / (ms * 1e-3) / 1e9
-            kern["%s %d-bit (not in step)" % (nm, bits)] = {"ms": round(ms, 4), "algorithmic_GBps": round(gbs, 1),
-                                                            "pct_hbm_peak": round(100 * gbs / HBM_PEAK_GBS, 1)}
-    del ksum
+        # Section 3.1 server-to-worker pull (not part of the timed step): the average as k in narrow fields;
+        # both the byte-aligned width (4 or 8 bits) and, where it differs, the narrowest one, ceil(log2(2W+1))
+        for bits in sorted({4 if W <= 7 else 8, binding.tg_sum_bits(W)}, reverse=True):
+            ksum = torch.empty((plan.tg_sum_bytes(bits),), dtype=torch.uint8, device="cuda")
+            ms = _timed(torch, stream, lambda: plan.tg_unpack_sum_pack(codes, bits, ksum), reps)
+            kern["unpack_sum_pack %d-bit (not in step)" % bits] = _rate(n * (0.25 * W + bits / 8.0), ms)
+            ms = _timed(torch, stream, lambda: plan.tg_decode_sum(W, ksum, bits, s_shared, avg), reps)
+            kern["decode_sum %d-bit (not in step)" % bits] = _rate(n * (bits / 8.0 + 4.0), ms)
+            del ksum
 
-    # Section 3.1, toward 32/log2(3): the base-3 container, five ternary values per byte (not in the step)
-    codes3 = [torch.empty((plan.packed_bytes_base3,), dtype=torch.uint8, device="cuda") for _ in range(W)]
-    for nm, fn, nbytes in (("ternarize_pack_base3", lambda: plan.tg_ternarize_pack_base3(grads, tau, s_shared, wl.seed, wl.step, codes3), W * 4.2),
-                           ("unpack_average_base3", lambda: plan.tg_unpack_average_base3(codes3, s_shared, avg), 0.2 * W + 4.0)):
-        for _ in range(2):
-            fn()
-        e0.record(stream)
-        for _ in range(reps):
-            fn()
-        e1.record(stream)
-        torch.cuda.synchronize()
-        ms = e0.elapsed_time(e1) / reps
-        gbs = n * nbytes / (ms * 1e-3) / 1e9
-        kern["%s (not in step)" % nm] = {"ms": round(ms, 4), "algorithmic_GBps": round(gbs, 1),
-                                         "pct_hbm_peak": round(100 * gbs / HBM_PEAK_GBS, 1)}
-    del codes3
+        # Section 3.1, toward 32/log2(3): the base-3 container, five ternary values per byte (not in the step)
+        codes3 = [torch.empty((plan.packed_bytes_base3,), dtype=torch.uint8, device="cuda") for _ in range(W)]
+        ms = _timed(torch, stream, lambda: plan.tg_ternarize_pack_base3(grads, tau, s_shared, wl.seed, wl.step, codes3), reps)
+        kern["ternarize_pack_base3 (not in step)"] = _rate(n * W * 4.2, ms)
+        ms = _timed(torch, stream, lambda: plan.tg_unpack_average_base3(codes3, s_shared, avg), reps)
+        kern["unpack_average_base3 (not in step)"] = _rate(n * (0.2 * W + 4.0), ms)
+        del codes3
 
-    # Algorithm 1's server line without scaler sharing (not part of the timed step): every worker's own scaler
-    for _ in range(2):
-        plan.tg_unpack_average_scalers(codes, s_local, avg)
-    e0.record(stream)
-    for _ in range(reps):
-        plan.tg_unpack_average_scalers(codes, s_local, avg)
-    e1.record(stream)
-    torch.cuda.synchronize()
-    us_ms = e0.elapsed_time(e1) / reps
-    us_gbs = n * (4.0 + 0.25 * W) / (us_ms * 1e-3) / 1e9
-    kern["unpack_average_scalers (not in step)"] = {"ms": round(us_ms, 4), "algorithmic_GBps": round(us_gbs, 1),
-                                                    "pct_hbm_peak": round(100 * us_gbs / HBM_PEAK_GBS, 1)}
+        # Algorithm 1's server line without scaler sharing (not part of the timed step)
+        ms = _timed(torch, stream, lambda: plan.tg_unpack_average_scalers(codes, s_local, avg), reps)
+        kern["unpack_average_scalers (not in step)"] = _rate(n * (4.0 + 0.25 * W), ms)
 
-    # Section 4.2 variant (not part of the timed step): plain fp32 average, as used for a layer that is
-    # kept in floating point; timed here over the whole flat buffer to get a bandwidth figure
-    favg = torch.empty((n,), dtype=torch.float32, device="cuda")
-    for _ in range(2):
-        binding.tg_average_float(grads, n, favg)
-    e0.record(stream)
-    for _ in range(reps):
-        binding.tg_average_float(grads, n, favg)
-    e1.record(stream)
-    torch.cuda.synchronize()
-    fa_ms = e0.elapsed_time(e1) / reps
-    fa_gbs = n * (4.0 * W + 4.0) / (fa_ms * 1e-3) / 1e9
-    kern["average_float (not in step)"] = {"ms": round(fa_ms, 4), "algorithmic_GBps": round(fa_gbs, 1),
-                                           "pct_hbm_peak": round(100 * fa_gbs / HBM_PEAK_GBS, 1)}
-    del favg
+        # Section 4.2 variant (not part of the timed step): plain fp32 average, as used for a layer that is
+        # kept in floating point; timed here over the whole flat buffer to get a bandwidth figure
+        favg = torch.empty((n,), dtype=torch.float32, device="cuda")
+        ms = _timed(torch, stream, lambda: binding.tg_average_float(grads, n, favg), reps)
+        kern["average_float (not in step)"] = _rate(n * (4.0 * W + 4.0), ms)
+        del favg
 
-    dom = "ternarize_pack"
-    achieved = alg_bytes[dom] / (call_ms[dom] * 1e-3) / 1e9
-    roofline = {"bound": "hbm", "kernel": "tg::ternarize_pack_kernel", "achieved": round(achieved, 1),
-                "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
-                "traffic": traffic_from_profile(dom, args.workload),
-                "algorithmic_bytes_per_launch": alg_bytes[dom], "avg_launch_ms": round(call_ms[dom], 4),
-                # what the same traffic (4 B read + 1/4 B written per element) reaches with no arithmetic at all,
-                # 4 GiB per launch, from the committed `bench.py --ceilings` run: context for `frac`
-                "pattern_ceiling_GBps": pattern_ceiling()}
+    res = {"workload": "%s gradients, fp32, W=%d simulated workers on one GPU, n=%d, L=%d, c=%.1f"
+                       % (wl.name, W, n, L, wl.clip_c),
+           "value": round(in_bytes / (ms_per_step * 1e-3) / 1e9, 2), "unit": "GB/s",
+           "ms_per_step": round(ms_per_step, 4), "ms_per_step_graph_replay": round(ms_per_step_graph, 4),
+           "kernels": kern, "rooflines": rooflines}
+    plan.close()
+    return res, (wl, grads)
 
+
+def main():
+    args = parse()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU only (the W workers are W gradient buffers on one "
+              "device; no collectives). Re-run with --gpus 1.", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from paper_1705_07878_amd import binding, workloads
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    if args.ceilings:
+        print(json.dumps(ceilings(torch, n=args.ceilings_elements)))
+        return
+
+    head, (wl, grads) = measure(torch, np, binding, workloads, args.workload, args.steps, args.warmup, extras=True)
+    W = wl.n_workers
     out = {
         "metric": "ternarize+pack and unpack-average GB/s (fp32 in) and % HBM peak; ms/step",
-        "value": round(in_bytes / (ms_per_step * 1e-3) / 1e9, 2), "unit": "GB/s",
-        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
+        "value": head["value"], "unit": "GB/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": head["ms_per_step"],
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32",
         "data": "synthetic",
-        "config": {"workload": "%s gradients, fp32, W=%d simulated workers on one GPU, n=%d, L=%d, c=%.1f"
-                               % (wl.name, W, n, L, wl.clip_c)},
-        "ms_per_step_graph_replay": round(ms_per_step_graph, 4),
-        "kernels": kern, "roofline": roofline,
+        "config": {"workload": head["workload"]},
+        "ms_per_step_graph_replay": head["ms_per_step_graph_replay"],
+        "kernels": head["kernels"],
+        # the dominant kernel of the step; the second kernel the metric names follows under its own key
+        "roofline": head["rooflines"]["ternarize_pack"],
+        "roofline_unpack_average": head["rooflines"]["unpack_average"],
     }
 
     if not args.no_cpu_baseline:
         # bounded sample: the whole workload if W*n <= 2.6e8 element passes, else its first layers
         cap = 260_000_000 // W
-        if n <= cap:
+        if wl.n <= cap:
             sub, note = wl, "the whole step (4 calls, all %d workers) of this workload" % W
             host = [g.cpu().numpy() for g in grads]
         else:
@@ -364,9 +390,25 @@ def main():
                                    step=wl.step)
             note = "the whole step on the first %d elements of each of the %d workers" % (tot, W)
             host = [g[:tot].cpu().numpy() for g in grads]
+        del grads
+        torch.cuda.empty_cache()
         out["cpu_baseline"] = cpu_baseline(sub, host, note)
         out["cpu_baseline"]["value"] = round(out["cpu_baseline"]["value"], 3)
         out["cpu_baseline"]["seconds"] = round(out["cpu_baseline"]["seconds"], 2)
+        del host
+    else:
+        del grads
+        torch.cuda.empty_cache()
+
+    # the other target configurations, same run, same measurement (the four calls only)
+    others = {}
+    for key in [k for k in args.also.split(",") if k and k != args.workload]:
+        res, state = measure(torch, np, binding, workloads, key, args.steps, args.warmup, extras=False)
+        del state
+        torch.cuda.empty_cache()
+        others[key] = res
+    if others:
+        out["other_configs"] = others
 
     # a plain copy of known size, outside the timed region: the calibration kernel for --pmc runs
     cal_src = torch.empty(64 * 1024 * 1024, dtype=torch.float32, device="cuda").normal_()
@@ -375,7 +417,6 @@ def main():
     torch.cuda.synchronize()
 
     print(json.dumps(out))
-    plan.close()
 
 
 if __name__ == "__main__":

@@ -254,16 +254,6 @@ tg_status tg_unpack_average_base3(tg_plan* plan, int n_workers, const uint8_t* c
  * modulo 16 bytes, as the same slice of equally laid out flat buffers is; else TG_ERR_ALIGNMENT. */
 tg_status tg_average_float(int n_workers, int64_t n, const float* const* grads, float* avg, void* stream);
 
-/* Measurement aid, no part of the method: the memory access patterns of the kernels above with the
- * arithmetic taken out, on the same launch shape (one wave per 1024 floats, four 128-bit accesses
- * per lane), to find what the memory system sustains for them.
- *   kind  0 plain streaming read of src; 1 the same with non-temporal loads; 2 non-temporal write
- *         of dst; 3 copy src -> dst (non-temporal both ways); 4 non-temporal read of src with one
- *         dword written per 16 floats read (to thin): the traffic shape of tg_ternarize_pack
- *   src   dev [n] fp32 (kinds 0, 1, 3, 4), dst dev [n] fp32 (written by kinds 2, 3; kinds 0, 1, 4
- *         may write dst[0]), thin dev [n/16] uint32 (kind 4); n a multiple of 1024; 16-byte aligned */
-tg_status tg_probe(int kind, const float* src, float* dst, uint32_t* thin, int64_t n, void* stream);
-
 #ifdef __cplusplus
 }
 #endif

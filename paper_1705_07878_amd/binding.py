@@ -85,8 +85,6 @@ lib.tg_ternarize_pack_base3.argtypes = lib.tg_ternarize_pack.argtypes
 lib.tg_ternarize_pack_base3.restype = ctypes.c_int
 lib.tg_unpack_average_base3.argtypes = lib.tg_unpack_average.argtypes
 lib.tg_unpack_average_base3.restype = ctypes.c_int
-lib.tg_probe.argtypes = [ctypes.c_int, _vp, _vp, _vp, _i64, _vp]
-lib.tg_probe.restype = ctypes.c_int
 lib.tg_average_float.argtypes = [ctypes.c_int, _i64, _pp, _vp, _vp]
 lib.tg_average_float.restype = ctypes.c_int
 
@@ -162,10 +160,6 @@ def tg_describe_tables(offsets, max_workers: int = 1):
 def tg_average_float(grads: Sequence, n: int, avg, stream=None):
     gp, _keep = _ptr_array(grads)
     _check(lib.tg_average_float(len(grads), int(n), gp, _ptr(avg), _stream(stream)), "tg_average_float")
-
-
-def tg_probe(kind: int, src, dst, thin, n: int, stream=None):
-    _check(lib.tg_probe(int(kind), _ptr(src), _ptr(dst), _ptr(thin), int(n), _stream(stream)), "tg_probe")
 
 
 def tg_step_advance(step_dev, by: int = 1, stream=None):

@@ -12,7 +12,6 @@
 #include <vector>
 
 #include "tg_float.hpp"
-#include "tg_probe.hpp"
 #include "tg_stats.hpp"
 #include "tg_ternarize.hpp"
 #include "tg_unpack.hpp"
@@ -142,10 +141,18 @@ struct tg_plan {
 
 static int64_t sum_bytes(const tg_plan* p, int bits) { return ((p->n * bits + 7) / 8 + 15) / 16 * 16; }
 
+// store policy and tile spreading of the decoders' float4 sinks (measured best on 4 GB outputs)
+constexpr int kSinkPolicy = tg::ST_NT;
+constexpr int kSinkTileShift = 0;
+
 template <int SRC, int DST, int BITS = 0>
-static tg_status launch_unpack(const tg::UnpackArgs& a, void* stream) {
-    const int64_t blocks = (a.n_wave_tiles + tg::kBlock / tg::kWave - 1) / (tg::kBlock / tg::kWave);
-    hipLaunchKernelGGL((tg::unpack_average_kernel<true, SRC, DST, BITS>), dim3((unsigned)blocks), dim3(tg::kBlock), 0,
+static tg_status launch_unpack(tg::UnpackArgs& a, void* stream) {
+    constexpr bool scaling = DST == tg::DST_AVG || DST == tg::DST_UPDATE || DST == tg::DST_MOMENTUM;
+    a.tile_shift = scaling ? kSinkTileShift : 0;
+    // whole groups of 2^shift workgroups, each group covering 4 * 2^shift consecutive tiles
+    const int64_t per_group = (int64_t)tg::kTilesPerBlock << a.tile_shift;
+    const int64_t blocks = ((a.n_wave_tiles + per_group - 1) / per_group) << a.tile_shift;
+    hipLaunchKernelGGL((tg::unpack_average_kernel<kSinkPolicy, SRC, DST, BITS>), dim3((unsigned)blocks), dim3(tg::kBlock), 0,
                        (hipStream_t)stream, a);
     if (!hip_ok(hipGetLastError())) return TG_ERR_HIP;
     return TG_OK;
@@ -229,9 +236,11 @@ tg_status tg_plan_create(int64_t n_layers, const int64_t* offsets, int max_worke
     if (max_workers > TG_MAX_WORKERS) return TG_ERR_TOO_MANY_WORKERS;
 
     Tables T;
+    std::vector<int64_t> off;
     tg_plan* p = nullptr;
     try {
         build_tables(n_layers, offsets, max_workers, T);
+        off.assign(offsets, offsets + n_layers + 1);
         p = new tg_plan();
     } catch (const std::bad_alloc&) {
         return TG_ERR_ALLOC;
@@ -244,7 +253,6 @@ tg_status tg_plan_create(int64_t n_layers, const int64_t* offsets, int max_worke
     p->n_units = (int64_t)T.units.size();
     p->max_workers = max_workers;
 
-    const std::vector<int64_t> off(offsets, offsets + n_layers + 1);
     const size_t np = (size_t)p->n_segs * (size_t)max_workers;
     bool ok = upload(&p->d_off, off) && upload(&p->d_tile_info, T.tile_info) &&
               upload(&p->d_units, T.units) &&
@@ -281,10 +289,10 @@ static tg_status check_workers(const tg_plan* p, int n_workers) {
     return TG_OK;
 }
 
-tg_status tg_clip_stats(tg_plan* p, int n_workers, const float* const* grads, float c,
-                        float* tau, float* s_local, void* stream) {
-    tg_status st = check_workers(p, n_workers);
-    if (st != TG_OK) return st;
+// the two launches of the statistics pass, with the partial sums in the given workspace
+static tg_status clip_stats_launch(tg_plan* p, int n_workers, const float* const* grads, float c,
+                                   float* tau, float* s_local, double* psum, double* psq, float* pmax,
+                                   void* stream) {
     if (grads == nullptr || tau == nullptr || s_local == nullptr || std::isnan(c)) return TG_ERR_INVALID_ARG;
     tg::StatsArgs a{};
     for (int w = 0; w < n_workers; ++w) {
@@ -294,9 +302,9 @@ tg_status tg_clip_stats(tg_plan* p, int n_workers, const float* const* grads, fl
     }
     if (!aligned(tau, 4) || !aligned(s_local, 4)) return TG_ERR_ALIGNMENT;
     a.units = p->d_units;
-    a.psum = p->d_psum;
-    a.psq = p->d_psq;
-    a.pmax = p->d_pmax;
+    a.psum = psum;
+    a.psq = psq;
+    a.pmax = pmax;
     a.n_segs = p->n_segs;
     hipStream_t s = (hipStream_t)stream;
     hipLaunchKernelGGL(tg::clip_stats_partial_kernel, dim3((unsigned)p->n_units, (unsigned)n_workers),
@@ -306,9 +314,9 @@ tg_status tg_clip_stats(tg_plan* p, int n_workers, const float* const* grads, fl
     tg::StatsFinalArgs f{};
     f.off = p->d_off;
     f.layer_seg = p->d_layer_seg;
-    f.psum = p->d_psum;
-    f.psq = p->d_psq;
-    f.pmax = p->d_pmax;
+    f.psum = psum;
+    f.psq = psq;
+    f.pmax = pmax;
     f.tau = tau;
     f.s_local = s_local;
     f.n_segs = p->n_segs;
@@ -325,6 +333,13 @@ tg_status tg_clip_stats(tg_plan* p, int n_workers, const float* const* grads, fl
     }
     if (!hip_ok(hipGetLastError())) return TG_ERR_HIP;
     return TG_OK;
+}
+
+tg_status tg_clip_stats(tg_plan* p, int n_workers, const float* const* grads, float c,
+                        float* tau, float* s_local, void* stream) {
+    const tg_status st = check_workers(p, n_workers);
+    if (st != TG_OK) return st;
+    return clip_stats_launch(p, n_workers, grads, c, tau, s_local, p->d_psum, p->d_psq, p->d_pmax, stream);
 }
 
 tg_status tg_share_scalers(tg_plan* p, int n_workers, const float* s_local, float* s_shared, void* stream) {
@@ -418,7 +433,7 @@ tg_status tg_unpack_average_base3(tg_plan* p, int n_workers, const uint8_t* cons
     a.avg = avg;
     a.packed_bytes = base3_bytes(p);
     const int64_t blocks = (p->n + tg::kBase3Elems - 1) / tg::kBase3Elems;
-    hipLaunchKernelGGL((tg::unpack_average_base3_kernel<true, tg::DST_AVG>), dim3((unsigned)blocks),
+    hipLaunchKernelGGL((tg::unpack_average_base3_kernel<kSinkPolicy, tg::DST_AVG>), dim3((unsigned)blocks),
                        dim3(tg::kBase3Block), 0, (hipStream_t)stream, a);
     if (!hip_ok(hipGetLastError())) return TG_ERR_HIP;
     return TG_OK;
@@ -456,7 +471,7 @@ tg_status tg_unpack_average_scalers(tg_plan* p, int n_workers, const uint8_t* co
     a.s_workers = s_workers;
     a.avg = avg;
     const int64_t blocks = (a.n_wave_tiles + tg::kTilesPerBlock - 1) / tg::kTilesPerBlock;
-    hipLaunchKernelGGL((tg::unpack_average_scalers_kernel<true>), dim3((unsigned)blocks), dim3(tg::kBlock), 0,
+    hipLaunchKernelGGL((tg::unpack_average_scalers_kernel<kSinkPolicy>), dim3((unsigned)blocks), dim3(tg::kBlock), 0,
                        (hipStream_t)stream, a);
     if (!hip_ok(hipGetLastError())) return TG_ERR_HIP;
     return TG_OK;
@@ -580,29 +595,6 @@ tg_status tg_average_float(int n_workers, int64_t n, const float* const* grads, 
     if (blocks < 1) blocks = 1;
     if (blocks > 0x7FFFFFFF) return TG_ERR_INVALID_ARG;
     hipLaunchKernelGGL(tg::average_float_kernel, dim3((unsigned)blocks), dim3(tg::kBlock), 0, (hipStream_t)stream, a);
-    if (!hip_ok(hipGetLastError())) return TG_ERR_HIP;
-    return TG_OK;
-}
-
-tg_status tg_probe(int kind, const float* src, float* dst, uint32_t* thin, int64_t n, void* stream) {
-    if (kind < tg::PROBE_READ || kind > tg::PROBE_READ_THIN_WRITE || n < tg::kWaveTile || n % tg::kWaveTile != 0)
-        return TG_ERR_INVALID_ARG;
-    const bool reads = kind != tg::PROBE_WRITE_NT;
-    if ((reads && src == nullptr) || dst == nullptr || (kind == tg::PROBE_READ_THIN_WRITE && thin == nullptr))
-        return TG_ERR_INVALID_ARG;
-    if ((reads && !aligned(src, 16)) || !aligned(dst, 16) || (thin != nullptr && !aligned(thin, 4))) return TG_ERR_ALIGNMENT;
-    tg::ProbeArgs a{src, dst, thin, n / tg::kWaveTile};
-    const int64_t blocks = (a.n_tiles + tg::kBlock / tg::kWave - 1) / (tg::kBlock / tg::kWave);
-    if (blocks > 0x7FFFFFFF) return TG_ERR_INVALID_ARG;
-    const dim3 grid((unsigned)blocks), block(tg::kBlock);
-    hipStream_t s = (hipStream_t)stream;
-    switch (kind) {
-        case tg::PROBE_READ: hipLaunchKernelGGL(tg::probe_kernel<tg::PROBE_READ>, grid, block, 0, s, a); break;
-        case tg::PROBE_READ_NT: hipLaunchKernelGGL(tg::probe_kernel<tg::PROBE_READ_NT>, grid, block, 0, s, a); break;
-        case tg::PROBE_WRITE_NT: hipLaunchKernelGGL(tg::probe_kernel<tg::PROBE_WRITE_NT>, grid, block, 0, s, a); break;
-        case tg::PROBE_COPY_NT: hipLaunchKernelGGL(tg::probe_kernel<tg::PROBE_COPY_NT>, grid, block, 0, s, a); break;
-        default: hipLaunchKernelGGL(tg::probe_kernel<tg::PROBE_READ_THIN_WRITE>, grid, block, 0, s, a); break;
-    }
     if (!hip_ok(hipGetLastError())) return TG_ERR_HIP;
     return TG_OK;
 }

@@ -49,10 +49,7 @@ __global__ void __launch_bounds__(kBlock) average_float_kernel(const FloatAvgArg
         }
         const float4 o = make_float4((float)(s0 / dW), (float)(s1 / dW),
                                      (float)(s2 / dW), (float)(s3 / dW));
-        __builtin_nontemporal_store(o.x, p.avg + i);
-        __builtin_nontemporal_store(o.y, p.avg + i + 1);
-        __builtin_nontemporal_store(o.z, p.avg + i + 2);
-        __builtin_nontemporal_store(o.w, p.avg + i + 3);
+        store_stream(p.avg + i, o);
     } else {
         for (int64_t e = i; e < p.n; ++e) average_float_one(p, e, dW);
     }

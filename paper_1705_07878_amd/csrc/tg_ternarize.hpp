@@ -15,7 +15,15 @@
 
 #include "tg_common.hpp"
 
+#ifndef TG_RNG_BITS
+#define TG_RNG_BITS 16
+#endif
+
 namespace tg {
+
+// u = (2r + 1) / 2^(BITS+1) for the BITS-bit random field r: the threshold u * s is formed as
+// fma(r, 2 * sF, sF) with sF = s * 2^-(BITS+1)
+constexpr float kFieldScale = TG_RNG_BITS == 16 ? 0x1p-17f : 0x1p-25f;
 
 struct TernArgs {
     const float* grads[kMaxWorkers];
@@ -113,6 +121,7 @@ __device__ __forceinline__ void tile_code_bytes(const TernArgs& p, const int w, 
     const float tau0 = tau_w[l0];
     const float s0 = p.s_shared[l0];
 
+#if TG_RNG_BITS == 16
     // Philox blocks of this tile: q0 .. q0+127; lane computes q0 + 64P + 32*par + (lane>>1)
     float rf[4][4];                // random fields of the lane's elements, quarter k, as floats
     const uint64_t q = (uint64_t)(e0 >> 3) + (uint32_t)(32 * par + (lane >> 1));
@@ -133,6 +142,20 @@ __device__ __forceinline__ void tile_code_bytes(const TernArgs& p, const int w, 
         rf[2 * P + 1][0] = (float)(b0 & 0xFFFFu), rf[2 * P + 1][1] = (float)(b0 >> 16);
         rf[2 * P + 1][2] = (float)(b1 & 0xFFFFu), rf[2 * P + 1][3] = (float)(b1 >> 16);
     }
+#else
+    // one 32-bit word per element, its top 24 bits the random field: block q covers the four
+    // consecutive elements 4q .. 4q+3, i.e. one float4 of one lane; the lane computes its own four blocks
+    (void)par;
+    float rf[4][4];
+    const uint64_t q = (uint64_t)(e0 >> 2) + (uint32_t)lane;
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        const uint64_t qq = q + 64 * k;
+        const U4 R = philox4x32_10((uint32_t)qq, (uint32_t)(qq >> 32), worker, step, p.key0, p.key1);
+        rf[k][0] = (float)(R.x >> 8), rf[k][1] = (float)(R.y >> 8);
+        rf[k][2] = (float)(R.z >> 8), rf[k][3] = (float)(R.w >> 8);
+    }
+#endif
 
     // (a tile entirely past the end needs no special case: its elements read as 0 and its table
     // entry names the last layer, so it encodes to zeros; an early exit here would only keep the
@@ -140,7 +163,7 @@ __device__ __forceinline__ void tile_code_bytes(const TernArgs& p, const int w, 
     if (whole) {
         // ---- the tile lies inside layer l0 ----
         const float tau = tau0;
-        const float s17 = s0 * 0x1p-17f;
+        const float s17 = s0 * kFieldScale;
         const float s16 = s17 * 2.0f;
 #pragma unroll
         for (int k = 0; k < 4; ++k) b[k] = encode4(v[k], rf[k], tau, s16, s17);
@@ -164,14 +187,14 @@ __device__ __forceinline__ void tile_code_bytes(const TernArgs& p, const int w, 
                 // no lane's four elements straddle a boundary (buckets that are multiples of four
                 // elements): one tau and one s per lane
                 const float tau = l[0] == l0 ? tau0 : tau_w[l[0]];
-                const float s17 = (l[0] == l0 ? s0 : p.s_shared[l[0]]) * 0x1p-17f;
+                const float s17 = (l[0] == l0 ? s0 : p.s_shared[l[0]]) * kFieldScale;
                 b[k] = encode4(v[k], rf[k], tau, s17 * 2.0f, s17);
             } else {
                 float tau[4], s17[4];
 #pragma unroll
                 for (int i = 0; i < 4; ++i) {
                     tau[i] = l[i] == l0 ? tau0 : tau_w[l[i]];
-                    s17[i] = (l[i] == l0 ? s0 : p.s_shared[l[i]]) * 0x1p-17f;
+                    s17[i] = (l[i] == l0 ? s0 : p.s_shared[l[i]]) * kFieldScale;
                 }
                 b[k] = encode4v(v[k], rf[k], tau, s17);
             }

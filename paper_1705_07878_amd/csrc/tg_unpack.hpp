@@ -36,6 +36,7 @@ struct UnpackArgs {
     int64_t packed_bytes;
     int32_t n_layers;
     int32_t n_workers;
+    int32_t tile_shift;         // log2 of the distance, in tiles, between the tiles of one workgroup (see TileMap)
 };
 
 struct Nib {
@@ -83,16 +84,29 @@ __device__ __forceinline__ float4 scale4(const uint32_t d, const float sc) {
     return o;
 }
 
-template <bool NT>
+enum { ST_PLAIN = 0, ST_NT = 1, ST_SC1 = 2, ST_SC0SC1 = 3 };     // cache policy of the float4 stores
+
+template <int POL>
 __device__ __forceinline__ void store4(float* dst, const float4 v) {
-    if (NT) {
-        __builtin_nontemporal_store(v.x, dst);
-        __builtin_nontemporal_store(v.y, dst + 1);
-        __builtin_nontemporal_store(v.z, dst + 2);
-        __builtin_nontemporal_store(v.w, dst + 3);
-    } else {
-        *reinterpret_cast<float4*>(dst) = v;
-    }
+    const f32x4 t = {v.x, v.y, v.z, v.w};
+    if (POL == ST_NT) store_stream(dst, v);
+    else if (POL == ST_SC1) asm volatile("global_store_dwordx4 %0, %1, off sc1" ::"v"(dst), "v"(t) : "memory");
+    else if (POL == ST_SC0SC1) asm volatile("global_store_dwordx4 %0, %1, off sc0 sc1" ::"v"(dst), "v"(t) : "memory");
+    else *reinterpret_cast<float4*>(dst) = v;
+}
+
+// Which tiles a workgroup owns.  Its j-th tile is base + (j << shift): consecutive tiles for shift 0;
+// for shift > 0 the workgroups of a group of 2^shift share 4 * 2^shift consecutive tiles, workgroup r
+// of the group taking the tiles r, r + 2^shift, r + 2 * 2^shift, r + 3 * 2^shift of them, so that the
+// stores a wave issues one after the other lie 2^shift tiles (4 KiB each) apart.
+struct TileMap {
+    int64_t base;
+    int shift;
+    __device__ __forceinline__ int64_t at(const int j) const { return base + ((int64_t)j << shift); }
+};
+__device__ __forceinline__ TileMap tile_map(const int64_t block, const int shift, const int tiles_per_block) {
+    const int64_t group = block >> shift, r = block & (((int64_t)1 << shift) - 1);
+    return TileMap{((group * tiles_per_block) << shift) + r, shift};
 }
 
 // w - eta * avg, one rounding
@@ -196,7 +210,7 @@ __device__ __forceinline__ void sum_codes(const int W, uint32_t D[4], LoadCodes 
 // order (256 dwords); the NWAVES waves write the NTILES tiles quarter by quarter, wave j the
 // quarters j, j + NWAVES, ..., so that every store step of the workgroup covers NWAVES KiB
 // contiguous.  Measured 6 - 10 % faster than each wave storing its own tile.
-template <bool NT, int DST, int NWAVES, int NTILES>
+template <int POL, int DST, int NWAVES, int NTILES>
 struct Emit {
     static constexpr int kSteps = 4 * NTILES / NWAVES;
     static constexpr bool MOMENTUM = DST == DST_MOMENTUM;
@@ -209,12 +223,12 @@ struct Emit {
     // Everything that depends on nothing but the tile indices is fetched first, before the codes are
     // summed and long before the barrier: the weights (and velocities), and the layer and scale of the
     // tiles this wave will write.
-    __device__ __forceinline__ void prefetch(const UnpackArgs& p, const int64_t tile0, const int wave, const int lane) {
+    __device__ __forceinline__ void prefetch(const UnpackArgs& p, const TileMap tm, const int wave, const int lane) {
         const float fW = (float)p.n_workers;
 #pragma unroll
         for (int i = 0; i < kSteps; ++i) {
             const int q = wave + i * NWAVES;
-            const int64_t tile = tile0 + (q >> 2);
+            const int64_t tile = tm.at(q >> 2);
             const int64_t te0 = tile * kWaveTile;
             if (UPDATE) {
                 const int64_t e = te0 + 256 * (q & 3) + 4 * lane;
@@ -247,21 +261,21 @@ struct Emit {
             const float4 v = vv[i];
             o = make_float4(__builtin_fmaf(p.mu, v.x, o.x), __builtin_fmaf(p.mu, v.y, o.y),
                             __builtin_fmaf(p.mu, v.z, o.z), __builtin_fmaf(p.mu, v.w, o.w));
-            store4<NT>(p.velocity + e, o);
+            store4<POL>(p.velocity + e, o);
         }
         if (UPDATE) o = apply4(wv[i], o, p.eta);
-        store4<NT>(p.avg + e, o);
+        store4<POL>(p.avg + e, o);
     }
 
     __device__ __forceinline__ void store(const UnpackArgs& p, const uint32_t (*kb)[kWaveTile / 4],
-                                          const int64_t tile0, const int wave, const int lane) const {
+                                          const TileMap tm, const int wave, const int lane) const {
         const float fW = (float)p.n_workers;
 #pragma unroll
         for (int i = 0; i < kSteps; ++i) {
             const int q = wave + i * NWAVES;
             const int t = q >> 2;
-            const int64_t tile = tile0 + t;
-            if (tile >= p.n_wave_tiles) break;
+            const int64_t tile = tm.at(t);
+            if (tile >= p.n_wave_tiles) continue;
             const int xq = 256 * (q & 3) + 4 * lane;           // position inside the tile
             const int64_t te0 = tile * kWaveTile;
             const int64_t e = te0 + xq;
@@ -301,7 +315,7 @@ struct Emit {
                     if (UPDATE && e + k < p.n) o[k] = __builtin_fmaf(-p.eta, o[k], p.avg[e + k]);
                 }
                 if (e + 3 < p.n) {
-                    store4<NT>(p.avg + e, make_float4(o[0], o[1], o[2], o[3]));
+                    store4<POL>(p.avg + e, make_float4(o[0], o[1], o[2], o[3]));
                 } else {
 #pragma unroll
                     for (int k = 0; k < 4; ++k)
@@ -312,21 +326,21 @@ struct Emit {
     }
 };
 
-// A workgroup owns 4 consecutive tiles.  Wave j sums the codes of tile j (one short-lived pass,
+// A workgroup owns 4 tiles (see TileMap).  Wave j sums the codes of its j-th tile (one short-lived pass,
 // every table lookup a scalar load); the scaling sinks then write the tiles together (see Emit).
-template <bool NT, int SRC, int DST, int BITS = 0>
+template <int POL, int SRC, int DST, int BITS = 0>
 __global__ void __launch_bounds__(kBlock) unpack_average_kernel(const UnpackArgs p) {
     __shared__ uint32_t lds[kTilesPerBlock][kWaveTile / 4];   // 1 KiB per tile
 
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = wave_uniform(threadIdx.x >> 6);
-    const int64_t tile0 = (int64_t)blockIdx.x * kTilesPerBlock;
-    const int64_t wt = tile0 + wave;
+    const TileMap tm = tile_map(blockIdx.x, p.tile_shift, kTilesPerBlock);
+    const int64_t wt = tm.at(wave);
     const bool valid = wt < p.n_wave_tiles;
     const int64_t e0 = wt * kWaveTile;
 
-    Emit<NT, DST, kTilesPerBlock, kTilesPerBlock> emit;
-    if (DST != DST_K4 && DST != DST_K8 && DST != DST_KB) emit.prefetch(p, tile0, wave, lane);
+    Emit<POL, DST, kTilesPerBlock, kTilesPerBlock> emit;
+    if (DST != DST_K4 && DST != DST_K8 && DST != DST_KB) emit.prefetch(p, tm, wave, lane);
 
     uint32_t D[4] = {0u, 0u, 0u, 0u};
     if (valid) {
@@ -405,7 +419,7 @@ __global__ void __launch_bounds__(kBlock) unpack_average_kernel(const UnpackArgs
     // ---- sinks that scale: the bytes go through LDS (a 64 x 16 -> 256 x 4 transpose per tile) ----
     *reinterpret_cast<uint4*>(&lds[wave][4 * lane]) = make_uint4(D[0], D[1], D[2], D[3]);
     __syncthreads();
-    emit.store(p, lds, tile0, wave, lane);
+    emit.store(p, lds, tm, wave, lane);
 }
 
 // ---- base-3 container (five ternary values per byte) as the source ----
@@ -416,7 +430,7 @@ __global__ void __launch_bounds__(kBlock) unpack_average_kernel(const UnpackArgs
 // bytes go to LDS in element order and the tiles are written cooperatively.
 constexpr int kBase3Chunk = 5;   // workers per 4-bit counter
 
-template <bool NT, int DST>
+template <int POL, int DST>
 __global__ void __launch_bounds__(kBase3Block) unpack_average_base3_kernel(const UnpackArgs p) {
     __shared__ uint16_t lut[256];
     __shared__ uint32_t kb[kBase3Waves][kWaveTile / 4];
@@ -427,8 +441,10 @@ __global__ void __launch_bounds__(kBase3Block) unpack_average_base3_kernel(const
     const int W = p.n_workers;
     const int64_t tile0 = (int64_t)blockIdx.x * kBase3Waves;
 
-    Emit<NT, DST, kBase3Waves, kBase3Waves> emit;
-    emit.prefetch(p, tile0, wave, lane);
+    // the five tiles of a workgroup are those of its 1024 consecutive code bytes: no spreading
+    const TileMap tm = {tile0, 0};
+    Emit<POL, DST, kBase3Waves, kBase3Waves> emit;
+    emit.prefetch(p, tm, wave, lane);
 
     // this thread's dword of every worker (threads 256..319 only take part in the stores)
     const int64_t byte0 = (int64_t)blockIdx.x * 1024 + 4 * (t & 255);
@@ -489,7 +505,7 @@ __global__ void __launch_bounds__(kBase3Block) unpack_average_base3_kernel(const
         dst[0] = D[0], dst[1] = D[1], dst[2] = D[2], dst[3] = D[3], dst[4] = H[0];
     }
     __syncthreads();
-    emit.store(p, kb, tile0, wave, lane);
+    emit.store(p, kb, tm, wave, lane);
 }
 
 // ---- the server line of Algorithm 1 without scaler sharing: avg = (1/N) sum_i s^(i) t_i ----
@@ -498,7 +514,7 @@ __global__ void __launch_bounds__(kBase3Block) unpack_average_base3_kernel(const
 // variant about as ALU- as memory-bound.  One wave per tile; lane L owns the 16 consecutive elements
 // of its code dword, and the 16 results go through LDS so that the wave stores whole float4s,
 // 1 KiB contiguous per store.
-template <bool NT>
+template <int POL>
 __global__ void __launch_bounds__(kBlock) unpack_average_scalers_kernel(const UnpackArgs p) {
     __shared__ float lds[kTilesPerBlock][kWaveTile];     // 4 KiB per tile
 
@@ -579,7 +595,7 @@ __global__ void __launch_bounds__(kBlock) unpack_average_scalers_kernel(const Un
         const float4 v = *reinterpret_cast<const float4*>(row + x);
         const int64_t e = e0 + x;
         if (e + 3 < p.n) {
-            store4<NT>(p.avg + e, v);
+            store4<POL>(p.avg + e, v);
         } else {
             const float o[4] = {v.x, v.y, v.z, v.w};
 #pragma unroll

@@ -29,6 +29,15 @@ def pytest_collection_modifyitems(config, items):
             it.add_marker(skip)
 
 
+def pytest_terminal_summary(terminalreporter):
+    """worst tau / s_local relative error against the oracle seen by the GPU parity tests"""
+    worst = getattr(sys.modules.get("parity_util"), "WORST", None)
+    if worst:
+        terminalreporter.write_sep("-", "worst relative error of the statistics vs the oracle (bound: 1e-6)")
+        for what in sorted(worst):
+            terminalreporter.write_line("%-40s %.3e" % (what, worst[what]))
+
+
 @pytest.fixture(scope="session")
 def oracle():
     import oracle as o

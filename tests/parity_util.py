@@ -1,8 +1,8 @@
 """Shared helpers of the GPU parity tests: run the HIP path through the C ABI
 and compare it with the CPU oracle on the same inputs.
 
-Protocol: (i) tau / s_local / s_shared within 1e-6 relative (absolute floor
-1e-6 * max|g| of the layer, for layers whose sigma is 0 or nearly so);
+Protocol: (i) tau / s_local within 1e-6 relative, s_shared exact (see
+stats_tolerance for the one regime where a relative bound cannot hold);
 (ii) the ORACLE's tau and s_shared are fed to both sides, then code buffers are
 compared byte for byte; (iii) the same codes and scaler go to both decoders,
 averages within 1e-6 relative and zeros exact.
@@ -82,28 +82,71 @@ def assert_update_close(got, want, w0, avg):
     assert np.all(err <= REL * scale), float((err / np.maximum(scale, 1e-300)).max())
 
 
-def layer_max_abs(g, off):
-    """max |g| of every layer (0 for an empty one)"""
+# worst relative error seen per quantity, over the layers held to the relative bound; printed at
+# the end of a test session (tests/conftest.py) and by smoke()
+WORST = {}
+
+
+def note_worst(what, value):
+    WORST[what] = max(WORST.get(what, 0.0), float(value))
+
+
+def layer_mean_minus_first(g, off):
+    """|mean - first element| of every layer (0 for an empty one), in fp64"""
     off = np.asarray(off, np.int64)
     out = np.zeros(off.size - 1, np.float64)
     full = np.flatnonzero(off[1:] > off[:-1])
     if full.size:
-        out[full] = np.maximum.reduceat(np.abs(g), off[full])        # consecutive non-empty layers tile [0, n)
+        # consecutive non-empty layers tile [0, n)
+        sums = np.add.reduceat(g, off[full], dtype=np.float64)
+        out[full] = np.abs(sums / (off[full + 1] - off[full]) - g[off[full]].astype(np.float64))
     return out
 
 
-def assert_stats_close(got, want, grads_np, off, what):
+def stats_tolerance(want, g, off, c):
+    """Allowed |got - want| per layer for tau and s_local of one worker, and the layers held to the
+    pure relative bound.
+
+    The statistics pass takes sum(g - K) and sum((g - K)^2) in fp64 about the pivot K = first element
+    of the layer, in one read.  With gamma <= 3e-14 the relative error of each sum (at most 256 serial
+    additions per thread, then a tree), the variance sigma^2 = S2/n - (S1/n)^2 carries an absolute error
+    of at most 3 gamma (sigma^2 + d^2), d = mean - K, so
+        |d sigma| / sigma <= 1.5 gamma (1 + d^2 / sigma^2)      and always      |d sigma| <= sqrt(3 gamma) (sigma + |d|).
+    Hence: wherever sigma >= 1e-3 |d| (every layer whose first element is not a million-sigma outlier)
+    the error is below 5e-8 relative and the test demands 1e-6 RELATIVE, nothing else.  Only for a
+    layer with sigma < 1e-3 |d| is the bound absolute: c * 1e-6 * |d|  (sqrt(3 gamma) = 3e-7).  Since the
+    first element alone contributes d^2 / n to the variance, sigma >= |d| / sqrt(n): that regime needs a
+    layer of more than 10^6 elements whose first element carries nearly all of its variance.
+    """
+    want = np.asarray(want, np.float64)
+    d = layer_mean_minus_first(g, off)
+    finite = np.isfinite(want)
+    sigma = np.where(finite, want, 0.0) / c if (c > 0 and np.isfinite(c)) else np.zeros_like(want)
+    relative = finite & (sigma >= 1e-3 * d)
+    tol = np.where(relative, REL * np.abs(np.where(finite, want, 0.0)), REL * abs(c) * d)
+    return tol, relative
+
+
+def assert_stats_close(got, want, grads_np, off, what, c, want_tau=None):
+    """tau or s_local [W][L] against the oracle's.  want_tau: the oracle's tau when `want` is s_local
+    (the regime of a layer is decided by its sigma = tau / c)."""
     got = np.asarray(got, np.float64)
     want = np.asarray(want, np.float64)
     assert got.shape == want.shape
+    noclip = not (c > 0 and np.isfinite(c))
     for w in range(want.shape[0]):
         a, b = got[w], want[w]
-        inf = np.isinf(b)
-        assert np.array_equal(a[inf], b[inf]), (what, w)
-        floor = REL * layer_max_abs(grads_np[w], off)
-        af, bf = np.where(inf, 0.0, a), np.where(inf, 0.0, b)
-        bad = ~inf & ~(np.abs(af - bf) <= np.maximum(REL * np.abs(bf), floor))   # a NaN is bad too
+        if noclip:
+            # tau = +inf and s_local = max|g|: exact on both sides
+            assert np.array_equal(a, b), (what, w)
+            continue
+        tol, relative = stats_tolerance(b if want_tau is None else want_tau[w], grads_np[w], off, c)
+        err = np.abs(a - b)
+        bad = ~(err <= tol)                                              # a NaN is bad too
         assert not bad.any(), (what, w, int(np.flatnonzero(bad)[0]), a[bad][0], b[bad][0])
+        nz = relative & (b != 0)
+        if nz.any():
+            note_worst(what + " rel.err", (err[nz] / np.abs(b[nz])).max())
 
 
 def assert_avg_close(got, want):
@@ -128,8 +171,8 @@ def full_parity(oracle, binding, off, grads_np, c=2.5, seed=0, step=0, worker_ba
         o_tau, o_sloc = zip(*[oracle.clip_stats(g, off, c) for g in grads_np])
         o_tau, o_sloc = np.stack(o_tau), np.stack(o_sloc)
         g_tau, g_sloc = gpu_clip_stats(plan, gd, c)
-        assert_stats_close(g_tau, o_tau, grads_np, off, "tau")
-        assert_stats_close(g_sloc, o_sloc, grads_np, off, "s_local")
+        assert_stats_close(g_tau, o_tau, grads_np, off, "tau", c)
+        assert_stats_close(g_sloc, o_sloc, grads_np, off, "s_local", c, want_tau=o_tau)
         # Eq. 4 is exact
         o_s = oracle.share_scalers(o_sloc)
         assert np.array_equal(gpu_share(plan, o_sloc), o_s)

@@ -75,8 +75,6 @@ def test_null_plan_is_rejected(binding):
     assert binding.lib.tg_ternarize_pack_base3(None, 1, 0, None, None, None, 0, 0, None, None) == binding.TG_ERR_INVALID_ARG
     assert binding.lib.tg_unpack_average_base3(None, 1, None, None, None, None) == binding.TG_ERR_INVALID_ARG
     assert binding.lib.tg_sum_bytes(None, 4) == -1
-    assert binding.lib.tg_probe(0, None, None, None, 1024, None) == binding.TG_ERR_INVALID_ARG
-    assert binding.lib.tg_probe(9, None, None, None, 1024, None) == binding.TG_ERR_INVALID_ARG
     assert [binding.lib.tg_sum_bits(N) for N in (0, 1, 2, 4, 8, 64, 65)] == [-1, 2, 3, 4, 5, 8, -1]
     assert binding.lib.tg_unpack_sum_pack(None, 1, None, 4, None, None) == binding.TG_ERR_INVALID_ARG
     assert binding.lib.tg_decode_sum(None, 1, None, 4, None, None, None) == binding.TG_ERR_INVALID_ARG

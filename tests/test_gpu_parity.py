@@ -576,32 +576,44 @@ def test_whole_step_replayed_from_a_hip_graph(oracle, binding):
         plan.close()
 
 
-def test_probe_kernels_move_what_they_claim(binding):
-    """the bandwidth probes: copy reproduces the source, write fills the destination, the thin stream
-    holds the XOR of each lane's 16 words, the read probes leave the destination alone"""
-    n = 1024 * 37
-    src = torch.randn(n, device="cuda")
-    dst = torch.full((n,), -7.0, device="cuda")
-    thin = torch.zeros(n // 16, dtype=torch.int32, device="cuda")
-    for kind in (0, 1):
-        binding.tg_probe(kind, src, dst, thin, n)
-    torch.cuda.synchronize()
-    assert bool((dst == -7.0).all())
-    binding.tg_probe(3, src, dst, thin, n)
-    torch.cuda.synchronize()
-    assert torch.equal(dst, src)
-    binding.tg_probe(2, src, dst, thin, n)
-    torch.cuda.synchronize()
-    assert dst.view(-1, 4)[:, :3].eq(torch.tensor([1.0, 2.0, 3.0], device="cuda")).all()
-    binding.tg_probe(4, src, dst, thin, n)
-    torch.cuda.synchronize()
-    w = src.cpu().numpy().view(np.uint32).reshape(-1, 4, 64, 4)          # tile, k, lane, word
-    want = np.bitwise_xor.reduce(np.bitwise_xor.reduce(w, axis=3), axis=1).reshape(-1)
-    assert np.array_equal(thin.cpu().numpy().view(np.uint32), want)
-    for bad in (lambda: binding.tg_probe(5, src, dst, thin, n), lambda: binding.tg_probe(0, src, dst, thin, 1000),
-                lambda: binding.tg_probe(4, src, dst, None, n), lambda: binding.tg_probe(1, src[1:], dst, thin, 1024)):
-        with pytest.raises(binding.TgError):
-            bad()
+def test_non_finite_and_subnormal_gradients_complete(oracle, binding):
+    """NaN / Inf gradients give unspecified values but never a fault: the four calls complete with
+    TG_OK, and a layer whose own inputs are finite is untouched by its neighbours: statistics and
+    codes equal the oracle's, only valid codes (00, 01, 11) appear.  Subnormal gradients are ordinary inputs."""
+    rng = np.random.default_rng(99)
+    off = _off([3000, 5000, 1029, 4096])
+    n = int(off[-1])
+    grads = _grads(rng, off, 2)
+    for g in grads:
+        g[7] = np.nan; g[100] = np.inf; g[2999] = -np.inf                   # layer 0: non-finite
+        g[8000:9029] = (rng.integers(-200, 200, size=1029) * 1.4e-45).astype(np.float32)   # layer 2: subnormals only
+    plan = binding.Plan(off, 2)
+    try:
+        gd = [dev(g) for g in grads]
+        tau, s_local = gpu_clip_stats(plan, gd, 2.5)
+        s_shared = gpu_share(plan, s_local)
+        codes = gpu_ternarize(plan, gd, tau, s_shared, 5, 6)
+        avg = gpu_unpack_average(plan, codes, s_shared)
+        torch.cuda.synchronize()
+        assert avg.shape == (n,)
+        # the finite layers (1, 2, 3) against the oracle, fed the same tau and s
+        fin = slice(3000, n)
+        off_f = off[1:] - 3000
+        for w, g in enumerate(grads):
+            o_tau, o_sl = oracle.clip_stats(g[fin], off_f, 2.5)
+            assert np.allclose(tau[w, 1:], o_tau, rtol=1e-6, atol=0) and np.allclose(s_local[w, 1:], o_sl, rtol=1e-6, atol=0)
+            c = codes[w][:(n + 3) // 4]
+            assert not ((c >> 1) & ~c & 0x55).any(), "code 10 produced"
+            # elements 3000.. start at a byte boundary (3000 = 4 * 750): the finite layers' bytes
+            # equal the oracle's when it is fed what the GPU was fed
+            tau_in = np.where(np.isfinite(tau[w]), tau[w], 0).astype(np.float32)
+            s_in = np.where(np.isfinite(s_shared), s_shared, 0).astype(np.float32)
+            g0 = np.where(np.isfinite(g), g, 0).astype(np.float32)
+            want = oracle.ternarize_pack(g0, off, tau_in, s_in, 5, 6, w)
+            assert np.array_equal(c[750:], want[750:])
+        assert np.isfinite(avg[3000:]).all()
+    finally:
+        plan.close()
 
 
 def test_argument_errors_on_device(binding):

@@ -70,7 +70,7 @@ __global__ void __launch_bounds__(kBlock) probe_kernel(const ProbeArgs p) {
     for (int k = 0; k < 4; ++k)
         x ^= __float_as_uint(v[k].x) ^ __float_as_uint(v[k].y) ^ __float_as_uint(v[k].z) ^ __float_as_uint(v[k].w);
     if (KIND == PROBE_READ_THIN_WRITE) {
-        store_through(p.thin + wt * kWave + lane, x);        // 256 contiguous bytes per wave, as the code stream
+        store_through<true>(p.thin + wt * kWave + lane, x);        // 256 contiguous bytes per wave, as the code stream
     } else if (x == 0x7FC12345u) {
         p.dst[0] = 1.0f;                                     // practically never: keeps the loads alive
     }

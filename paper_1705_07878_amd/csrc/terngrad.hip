@@ -387,14 +387,21 @@ static tg_status ternarize_launch(tg_plan* p, int n_workers, uint32_t worker_bas
     if (base3) {
         a.packed_bytes = base3_bytes(p);
         const int64_t b3 = (a.packed_bytes + 1023) / 1024;
-        hipLaunchKernelGGL(tg::ternarize_pack_base3_kernel, dim3((unsigned)b3, (unsigned)n_workers),
-                           dim3(tg::kBase3Block), 0, (hipStream_t)stream, a);
+        const dim3 g3((unsigned)b3, (unsigned)n_workers), t3(tg::kBase3Block);
+        if (a.packed_bytes * n_workers > tg::kCodeStreamNtFrom)
+            hipLaunchKernelGGL(tg::ternarize_pack_base3_kernel<true>, g3, t3, 0, (hipStream_t)stream, a);
+        else
+            hipLaunchKernelGGL(tg::ternarize_pack_base3_kernel<false>, g3, t3, 0, (hipStream_t)stream, a);
         if (!hip_ok(hipGetLastError())) return TG_ERR_HIP;
         return TG_OK;
     }
     const int64_t blocks = (a.n_wave_tiles + tg::kBlock / tg::kWave - 1) / (tg::kBlock / tg::kWave);
-    hipLaunchKernelGGL(tg::ternarize_pack_kernel, dim3((unsigned)blocks, (unsigned)n_workers),
-                       dim3(tg::kBlock), 0, (hipStream_t)stream, a);
+    // cache policy of the code stream by the size of the job (see store_through)
+    const dim3 grid((unsigned)blocks, (unsigned)n_workers), block(tg::kBlock);
+    if (a.packed_bytes * n_workers > tg::kCodeStreamNtFrom)
+        hipLaunchKernelGGL(tg::ternarize_pack_kernel<true>, grid, block, 0, (hipStream_t)stream, a);
+    else
+        hipLaunchKernelGGL(tg::ternarize_pack_kernel<false>, grid, block, 0, (hipStream_t)stream, a);
     if (!hip_ok(hipGetLastError())) return TG_ERR_HIP;
     return TG_OK;
 }

@@ -82,14 +82,19 @@ __device__ __forceinline__ void store_stream(float* p, const float4 v) {
     __builtin_nontemporal_store(t, reinterpret_cast<f32x4*>(p));
 }
 
-// Dword store of the thin code stream that accompanies the gradient read, with the nt and sc1
-// cache-policy bits.  Measured on 10^9 elements x 8 workers: sc1 alone, nt alone and both give the
-// encoder the same speed to 1 % (both: 5.37 ms, either alone: 5.40), and 4 % over a plain store;
-// but lines written WITHOUT nt slow down whatever kernel runs next (the decoder that follows in
-// the step took 1.04 ms instead of 0.97 ms after 2 GB of plain or sc1 stores, even with another
-// kernel or an idle gap in between), so nt is what matters for the step as a whole.
+// Dword store of the thin code stream that accompanies the gradient read.  Always with the sc1
+// cache-policy bit (4 % faster for the encoder than a plain store); with nt on top when the code
+// buffers of a launch are too large to stay in the 256 MB memory-side cache.  Measured with 8 workers
+// (encoder + the decoder that follows it, ms): 200 MB of codes 0.608 without nt / 0.655 with nt;
+// 266 MB (VGG-A shapes) 0.82 / 0.87; 300 MB 0.965 / 0.973; 500 MB 1.64 / 1.62; 2 GB 6.43 / 6.18 - 6.34.
+// Small jobs: the decoder finds the codes in the cache.  Large jobs: lines written WITHOUT nt slow down
+// whatever kernel runs next (the decoder took 1.04 ms instead of 0.97 ms after 2 GB of plain or sc1
+// stores, even with another kernel or an idle gap in between).
+constexpr int64_t kCodeStreamNtFrom = (int64_t)288 << 20;     // bytes of codes per launch
+template <bool NT>
 __device__ __forceinline__ void store_through(uint32_t* p, uint32_t v) {
-    asm volatile("global_store_dword %0, %1, off sc1 nt" ::"v"(p), "v"(v) : "memory");
+    if (NT) asm volatile("global_store_dword %0, %1, off sc1 nt" ::"v"(p), "v"(v) : "memory");
+    else asm volatile("global_store_dword %0, %1, off sc1" ::"v"(p), "v"(v) : "memory");
 }
 
 // value held by the neighbouring lane (lane ^ 1), via DPP quad_perm [1,0,3,2]

@@ -15,15 +15,13 @@
 
 #include "tg_common.hpp"
 
-#ifndef TG_RNG_BITS
-#define TG_RNG_BITS 16
-#endif
-
 namespace tg {
 
-// u = (2r + 1) / 2^(BITS+1) for the BITS-bit random field r: the threshold u * s is formed as
-// fma(r, 2 * sF, sF) with sF = s * 2^-(BITS+1)
-constexpr float kFieldScale = TG_RNG_BITS == 16 ? 0x1p-17f : 0x1p-25f;
+// u = (2r + 1) / 2^17 for the 16-bit random field r: the threshold u * s is formed as
+// fma(r, 2 * s17, s17) with s17 = s * 2^-17.  (A 24-bit field, one Philox word per element and twice
+// the Philox work, was measured: the encoder then becomes ALU-limited on the largest workload,
+// 5.41 ms instead of 5.34 - 5.36 ms for 8 x 10^9 elements, one point of HBM fraction.)
+constexpr float kFieldScale = 0x1p-17f;
 
 struct TernArgs {
     const float* grads[kMaxWorkers];
@@ -121,7 +119,6 @@ __device__ __forceinline__ void tile_code_bytes(const TernArgs& p, const int w, 
     const float tau0 = tau_w[l0];
     const float s0 = p.s_shared[l0];
 
-#if TG_RNG_BITS == 16
     // Philox blocks of this tile: q0 .. q0+127; lane computes q0 + 64P + 32*par + (lane>>1)
     float rf[4][4];                // random fields of the lane's elements, quarter k, as floats
     const uint64_t q = (uint64_t)(e0 >> 3) + (uint32_t)(32 * par + (lane >> 1));
@@ -142,20 +139,6 @@ __device__ __forceinline__ void tile_code_bytes(const TernArgs& p, const int w, 
         rf[2 * P + 1][0] = (float)(b0 & 0xFFFFu), rf[2 * P + 1][1] = (float)(b0 >> 16);
         rf[2 * P + 1][2] = (float)(b1 & 0xFFFFu), rf[2 * P + 1][3] = (float)(b1 >> 16);
     }
-#else
-    // one 32-bit word per element, its top 24 bits the random field: block q covers the four
-    // consecutive elements 4q .. 4q+3, i.e. one float4 of one lane; the lane computes its own four blocks
-    (void)par;
-    float rf[4][4];
-    const uint64_t q = (uint64_t)(e0 >> 2) + (uint32_t)lane;
-#pragma unroll
-    for (int k = 0; k < 4; ++k) {
-        const uint64_t qq = q + 64 * k;
-        const U4 R = philox4x32_10((uint32_t)qq, (uint32_t)(qq >> 32), worker, step, p.key0, p.key1);
-        rf[k][0] = (float)(R.x >> 8), rf[k][1] = (float)(R.y >> 8);
-        rf[k][2] = (float)(R.z >> 8), rf[k][3] = (float)(R.w >> 8);
-    }
-#endif
 
     // (a tile entirely past the end needs no special case: its elements read as 0 and its table
     // entry names the last layer, so it encodes to zeros; an early exit here would only keep the
@@ -202,6 +185,7 @@ __device__ __forceinline__ void tile_code_bytes(const TernArgs& p, const int w, 
     }
 }
 
+template <bool NT_CODES>
 __global__ void __launch_bounds__(kBlock) ternarize_pack_kernel(const TernArgs p) {
     __shared__ uint32_t lds[kBlock / kWave][kWave];   // 256 B per wave
 
@@ -223,7 +207,7 @@ __global__ void __launch_bounds__(kBlock) ternarize_pack_kernel(const TernArgs p
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
     const uint32_t dw = lds[wave][lane];
     const int64_t byte0 = (wt * kWaveTile >> 2) + 4 * lane;
-    if (byte0 < p.packed_bytes) store_through(reinterpret_cast<uint32_t*>(p.codes[blockIdx.y] + byte0), dw);
+    if (byte0 < p.packed_bytes) store_through<NT_CODES>(reinterpret_cast<uint32_t*>(p.codes[blockIdx.y] + byte0), dw);
 }
 
 // ---- base-3 container: five ternary values per byte (1.6 bits, toward 32/log2(3)) ----
@@ -239,6 +223,7 @@ __device__ __forceinline__ uint32_t base3_byte(const uint32_t digits10) {
     return d0 + 3u * d1 + 9u * d2 + 27u * d3 + 81u * d4;
 }
 
+template <bool NT_CODES>
 __global__ void __launch_bounds__(kBase3Block) ternarize_pack_base3_kernel(const TernArgs p) {
     __shared__ uint32_t lds[kBase3Waves * kWave];       // 1280 B of 2-bit codes
 
@@ -263,7 +248,7 @@ __global__ void __launch_bounds__(kBase3Block) ternarize_pack_base3_kernel(const
 #pragma unroll
     for (int qd = 0; qd < 4; ++qd) out |= base3_byte((uint32_t)(x >> (10 * qd)) & 0x3FFu) << (8 * qd);
     const int64_t byte0 = (int64_t)blockIdx.x * 1024 + 4 * t;
-    if (byte0 < p.packed_bytes) store_through(reinterpret_cast<uint32_t*>(p.codes[blockIdx.y] + byte0), out);
+    if (byte0 < p.packed_bytes) store_through<NT_CODES>(reinterpret_cast<uint32_t*>(p.codes[blockIdx.y] + byte0), out);
 }
 
 }  // namespace tg

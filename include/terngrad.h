@@ -71,7 +71,8 @@ typedef enum {
     TG_ERR_ALIGNMENT = -2,        /* a device pointer is not aligned as required      */
     TG_ERR_TOO_MANY_WORKERS = -3, /* n_workers > plan's max_workers or TG_MAX_WORKERS  */
     TG_ERR_HIP = -4,              /* a HIP call failed: see tg_last_hip_error()        */
-    TG_ERR_ALLOC = -5             /* host or device allocation failed                  */
+    TG_ERR_ALLOC = -5,            /* host or device allocation failed                  */
+    TG_ERR_TOO_LARGE = -6         /* the job exceeds TG_STATIC_SCRATCH_BYTES           */
 } tg_status;
 
 /* The paper trains with up to N = 64 workers (Section 4.1, LeNet). */
@@ -131,6 +132,26 @@ tg_status tg_describe_tables(int64_t n_layers, const int64_t* offsets, int max_w
  * +inf without clipping) and s_local = 0. */
 tg_status tg_clip_stats(tg_plan* plan, int n_workers, const float* const* grads, float c,
                         float* tau, float* s_local, void* stream);
+
+/* For callers that cannot allocate device memory or want no workspace tied to a plan: code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  tg_clip_stats with its
+ * per-segment partial sums in a fixed buffer of TG_STATIC_SCRATCH_BYTES that is part of the loaded
+ * library (static device memory, one copy per GPU, held until the process ends) instead of the
+ * plan's workspace.  Arguments and results are those of tg_clip_stats, bit for bit.  Between being
+ * called and returning it calls no hipMalloc, hipFree or other allocating routine (the address of
+ * the buffer on the plan's device was resolved in tg_plan_create).
+ *   - n_workers may exceed the plan's max_workers (up to TG_MAX_WORKERS): the plan's workspace is unused.
+ *   - The job must fit: tg_static_scratch_needed(plan, n_workers) <= TG_STATIC_SCRATCH_BYTES
+ *     (20 bytes per reduction segment and worker; the flat 10^9-element, 8-worker job needs 2.4 MB),
+ *     else TG_ERR_TOO_LARGE and nothing is launched.
+ *   - Every call on a GPU, from any plan, thread or stream, shares that GPU's one buffer: calls that
+ *     overlap on the device race.  Order them on one stream or with events.  The buffer keeps the
+ *     last call's partial sums; nothing in it has to be cleared between calls.
+ *   - The current device must be the plan's device. */
+#define TG_STATIC_SCRATCH_BYTES (8 * 1024 * 1024)
+int64_t tg_static_scratch_needed(const tg_plan* plan, int n_workers); /* bytes, or -1 for bad arguments */
+tg_status tg_clip_stats_static(tg_plan* plan, int n_workers, const float* const* grads, float c,
+                               float* tau, float* s_local, void* stream);
 
 /* Eq. 4: s_shared[l] = max_w s_local[w][l].
  *   s_local  dev [n_workers][L] in ; s_shared dev [L] out.

@@ -22,6 +22,8 @@ TG_ERR_ALIGNMENT = -2
 TG_ERR_TOO_MANY_WORKERS = -3
 TG_ERR_HIP = -4
 TG_ERR_ALLOC = -5
+TG_ERR_TOO_LARGE = -6
+TG_STATIC_SCRATCH_BYTES = 8 * 1024 * 1024
 TG_MAX_WORKERS = 64
 
 if not os.path.exists(LIB_PATH):
@@ -53,6 +55,10 @@ lib.tg_describe_tables.argtypes = [_i64, ctypes.POINTER(_i64), ctypes.c_int,
 lib.tg_describe_tables.restype = ctypes.c_int
 lib.tg_clip_stats.argtypes = [_vp, ctypes.c_int, _pp, ctypes.c_float, _vp, _vp, _vp]
 lib.tg_clip_stats.restype = ctypes.c_int
+lib.tg_clip_stats_static.argtypes = [_vp, ctypes.c_int, _pp, ctypes.c_float, _vp, _vp, _vp]
+lib.tg_clip_stats_static.restype = ctypes.c_int
+lib.tg_static_scratch_needed.argtypes = [_vp, ctypes.c_int]
+lib.tg_static_scratch_needed.restype = _i64
 lib.tg_share_scalers.argtypes = [_vp, ctypes.c_int, _vp, _vp, _vp]
 lib.tg_share_scalers.restype = ctypes.c_int
 lib.tg_ternarize_pack.argtypes = [_vp, ctypes.c_int, ctypes.c_uint32, _pp, _vp, _vp,
@@ -207,6 +213,14 @@ class Plan:
         gp, _keep = _ptr_array(grads)
         _check(lib.tg_clip_stats(self._h, len(grads), gp, float(c), _ptr(tau), _ptr(s_local),
                                  _stream(stream)), "tg_clip_stats")
+
+    def tg_clip_stats_static(self, grads: Sequence, c: float, tau, s_local, stream=None):
+        gp, _keep = _ptr_array(grads)
+        _check(lib.tg_clip_stats_static(self._h, len(grads), gp, float(c), _ptr(tau), _ptr(s_local),
+                                        _stream(stream)), "tg_clip_stats_static")
+
+    def tg_static_scratch_needed(self, n_workers: int) -> int:
+        return int(lib.tg_static_scratch_needed(self._h, int(n_workers)))
 
     def tg_share_scalers(self, n_workers: int, s_local, s_shared, stream=None):
         _check(lib.tg_share_scalers(self._h, int(n_workers), _ptr(s_local), _ptr(s_shared),

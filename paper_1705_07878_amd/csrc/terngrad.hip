@@ -8,6 +8,7 @@
 #include <cmath>
 #include <cstdlib>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <vector>
 
@@ -17,6 +18,13 @@
 #include "tg_unpack.hpp"
 
 static_assert(TG_MAX_WORKERS == tg::kMaxWorkers, "header and kernels disagree on the worker limit");
+
+// Workspace of tg_clip_stats_static: the per-segment partial sums, in device memory that exists from
+// the moment the library is loaded (every GPU the library runs on holds its own copy until the process
+// ends).  In host code this name is only a handle for hipGetSymbolAddress, never an address.
+#define TG_STATIC_SCRATCH_BYTES_IMPL (8 * 1024 * 1024)
+static __device__ __align__(256) unsigned char scratch[TG_STATIC_SCRATCH_BYTES_IMPL];
+static_assert(TG_STATIC_SCRATCH_BYTES_IMPL == TG_STATIC_SCRATCH_BYTES, "header and library disagree on the scratch size");
 
 namespace {
 
@@ -115,6 +123,24 @@ void build_tables(int64_t L, const int64_t* off, int max_workers, Tables& T) {
     }
 }
 
+// The address of `scratch` on the current device (each device has its own copy at its own address),
+// resolved once per device and kept.  Allocates nothing.
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[kMaxDevices] = {};
+
+bool scratch_address(int device, void** out) {
+    if (device < 0 || device >= kMaxDevices) return false;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (g_scratch_ptr[device] == nullptr) {
+        void* ptr = nullptr;
+        if (!hip_ok(hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch))) || ptr == nullptr) return false;
+        g_scratch_ptr[device] = ptr;
+    }
+    *out = g_scratch_ptr[device];
+    return true;
+}
+
 template <class T>
 bool upload(T** dst, const std::vector<T>& src) {
     const size_t bytes = (src.empty() ? 1 : src.size()) * sizeof(T);
@@ -130,6 +156,8 @@ bool aligned(const void* p, uintptr_t a) { return ((uintptr_t)p & (a - 1)) == 0;
 struct tg_plan {
     int64_t n_layers = 0, n = 0, packed_bytes = 0, n_tiles = 0, n_segs = 0, n_units = 0;
     int max_workers = 0;
+    int device = -1;                // the device that was current at tg_plan_create
+    void* d_scratch = nullptr;      // that device's copy of the static scratch array
     int64_t* d_off = nullptr;
     uint32_t* d_tile_info = nullptr;
     tg::StatUnit* d_units = nullptr;
@@ -191,6 +219,7 @@ const char* tg_strerror(int status) {
         case TG_ERR_TOO_MANY_WORKERS: return "too many workers for this plan";
         case TG_ERR_HIP: return "a HIP call failed (see tg_last_hip_error)";
         case TG_ERR_ALLOC: return "allocation failed";
+        case TG_ERR_TOO_LARGE: return "job too large for the static scratch buffer";
         default: return "unknown status";
     }
 }
@@ -244,6 +273,11 @@ tg_status tg_plan_create(int64_t n_layers, const int64_t* offsets, int max_worke
         p = new tg_plan();
     } catch (const std::bad_alloc&) {
         return TG_ERR_ALLOC;
+    }
+    // set-up work of tg_clip_stats_static, done here so that the call itself touches no runtime state
+    if (!hip_ok(hipGetDevice(&p->device)) || !scratch_address(p->device, &p->d_scratch)) {
+        delete p;
+        return TG_ERR_HIP;
     }
     p->n_layers = n_layers;
     p->n = T.n;
@@ -340,6 +374,27 @@ tg_status tg_clip_stats(tg_plan* p, int n_workers, const float* const* grads, fl
     const tg_status st = check_workers(p, n_workers);
     if (st != TG_OK) return st;
     return clip_stats_launch(p, n_workers, grads, c, tau, s_local, p->d_psum, p->d_psq, p->d_pmax, stream);
+}
+
+int64_t tg_static_scratch_needed(const tg_plan* p, int n_workers) {
+    if (p == nullptr || n_workers < 1 || n_workers > TG_MAX_WORKERS) return -1;
+    // [W][n_segs] doubles twice, then [W][n_segs] floats: every part starts on an 8-byte boundary
+    return p->n_segs * (int64_t)n_workers * (int64_t)(2 * sizeof(double) + sizeof(float));
+}
+
+tg_status tg_clip_stats_static(tg_plan* p, int n_workers, const float* const* grads, float c,
+                               float* tau, float* s_local, void* stream) {
+    if (p == nullptr || n_workers < 1) return TG_ERR_INVALID_ARG;
+    if (n_workers > TG_MAX_WORKERS) return TG_ERR_TOO_MANY_WORKERS;     // the plan's own workspace is not used
+    if (tg_static_scratch_needed(p, n_workers) > TG_STATIC_SCRATCH_BYTES) return TG_ERR_TOO_LARGE;
+    if (p->d_scratch == nullptr) return TG_ERR_HIP;
+    const size_t np = (size_t)p->n_segs * (size_t)n_workers;
+    double* psum = reinterpret_cast<double*>(p->d_scratch);
+    double* psq = psum + np;
+    float* pmax = reinterpret_cast<float*>(psq + np);
+    // every partial that the second kernel reads is written by the first one in this call: nothing in
+    // the array has to start at zero
+    return clip_stats_launch(p, n_workers, grads, c, tau, s_local, psum, psq, pmax, stream);
 }
 
 tg_status tg_share_scalers(tg_plan* p, int n_workers, const float* s_local, float* s_shared, void* stream) {

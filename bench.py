@@ -269,7 +269,10 @@ def measure(torch, np, binding, workloads, key, steps, warmup, extras):
     ms_per_step_graph = (time.perf_counter() - t0) * 1e3 / steps
     del graph
 
-    # per-call timing with events on the launch stream, over K more steps
+    # per-call timing with events on the launch stream, over K more steps (one untimed step first:
+    # the first launch after the graph's memory is released can stall for milliseconds)
+    step(0)
+    torch.cuda.synchronize()
     evs = [[torch.cuda.Event(enable_timing=True) for _ in range(5)] for _ in range(steps)]
     for t in range(steps):
         step(t, evs[t])

@@ -8,7 +8,8 @@
 //   int bench_probe(int kind, const float* src, float* dst, uint32_t* thin, int64_t n, void* stream)
 //     kind  0 plain streaming read of src; 1 the same with non-temporal loads; 2 non-temporal write
 //           of dst; 3 copy src -> dst (non-temporal both ways); 4 non-temporal read of src with one
-//           dword written per 16 floats read (to thin): the traffic shape of tg_ternarize_pack;
+//           dword written per 16 floats read (to thin): the traffic shape of tg_ternarize_pack, with the
+//           encoder's cache policy for a code stream of that size;
 //           5 the decoder's write pattern: workgroups of four waves own four tiles and write each
 //           tile together, a wave's four stores 4 KiB apart (non-temporal)
 //     src   dev [n] fp32 (kinds 0, 1, 3, 4), dst dev [n] fp32 (written by kinds 2, 3, 5; kinds 0, 1, 4
@@ -33,7 +34,7 @@ struct ProbeArgs {
     int64_t n_tiles;
 };
 
-template <int KIND>
+template <int KIND, bool NT_THIN = false>
 __global__ void __launch_bounds__(kBlock) probe_kernel(const ProbeArgs p) {
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = wave_uniform(threadIdx.x >> 6);
@@ -70,7 +71,7 @@ __global__ void __launch_bounds__(kBlock) probe_kernel(const ProbeArgs p) {
     for (int k = 0; k < 4; ++k)
         x ^= __float_as_uint(v[k].x) ^ __float_as_uint(v[k].y) ^ __float_as_uint(v[k].z) ^ __float_as_uint(v[k].w);
     if (KIND == PROBE_READ_THIN_WRITE) {
-        store_through<true>(p.thin + wt * kWave + lane, x);        // 256 contiguous bytes per wave, as the code stream
+        store_through<NT_THIN>(p.thin + wt * kWave + lane, x);     // 256 contiguous bytes per wave, as the code stream
     } else if (x == 0x7FC12345u) {
         p.dst[0] = 1.0f;                                     // practically never: keeps the loads alive
     }
@@ -96,7 +97,11 @@ extern "C" int bench_probe(int kind, const float* src, float* dst, uint32_t* thi
         case PROBE_READ_NT: hipLaunchKernelGGL(probe_kernel<PROBE_READ_NT>, grid, block, 0, s, a); break;
         case PROBE_WRITE_NT: hipLaunchKernelGGL(probe_kernel<PROBE_WRITE_NT>, grid, block, 0, s, a); break;
         case PROBE_COPY_NT: hipLaunchKernelGGL(probe_kernel<PROBE_COPY_NT>, grid, block, 0, s, a); break;
-        case PROBE_READ_THIN_WRITE: hipLaunchKernelGGL(probe_kernel<PROBE_READ_THIN_WRITE>, grid, block, 0, s, a); break;
+        case PROBE_READ_THIN_WRITE:
+            // cache policy of the thin stream by its size, as the encoder chooses it
+            if (n / 4 > kCodeStreamNtFrom) hipLaunchKernelGGL((probe_kernel<PROBE_READ_THIN_WRITE, true>), grid, block, 0, s, a);
+            else hipLaunchKernelGGL((probe_kernel<PROBE_READ_THIN_WRITE, false>), grid, block, 0, s, a);
+            break;
         default: hipLaunchKernelGGL(probe_kernel<PROBE_WRITE_NT_COOP>, grid, block, 0, s, a); break;
     }
     return hipGetLastError() == hipSuccess ? 0 : -4;

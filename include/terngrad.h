@@ -217,6 +217,13 @@ tg_status tg_unpack_update(tg_plan* plan, int n_workers, const uint8_t* const* c
 tg_status tg_unpack_average_scalers(tg_plan* plan, int n_workers, const uint8_t* const* codes,
                                     const float* s_workers, float* avg, void* stream);
 
+/* Tuning knob of tg_unpack_update and tg_unpack_update_momentum.  They have two kernels with
+ * bit-identical results: a workgroup-cooperative one (four tiles of 1024 elements per workgroup,
+ * faster while the weights fit the memory-side cache) and one with a wave per 256 elements (faster
+ * from about 1 GiB of weights on); mode 0 (the default) picks by the size of the model, 1 forces the
+ * first, 2 the second.  Applies to later calls on this plan.  TG_ERR_INVALID_ARG for other modes. */
+tg_status tg_plan_set_update_kernel(tg_plan* plan, int mode);
+
 /* The same with momentum (the optimizer of most experiments in Section 4):
  *   velocity[e] <- mu * velocity[e] + avg[e] ;  weights[e] <- weights[e] - eta * velocity[e]
  * (two fused multiply-adds; mu = 0 reproduces tg_unpack_update and leaves avg in velocity).

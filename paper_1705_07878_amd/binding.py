@@ -55,6 +55,8 @@ lib.tg_describe_tables.argtypes = [_i64, ctypes.POINTER(_i64), ctypes.c_int,
 lib.tg_describe_tables.restype = ctypes.c_int
 lib.tg_clip_stats.argtypes = [_vp, ctypes.c_int, _pp, ctypes.c_float, _vp, _vp, _vp]
 lib.tg_clip_stats.restype = ctypes.c_int
+lib.tg_plan_set_update_kernel.argtypes = [_vp, ctypes.c_int]
+lib.tg_plan_set_update_kernel.restype = ctypes.c_int
 lib.tg_clip_stats_static.argtypes = [_vp, ctypes.c_int, _pp, ctypes.c_float, _vp, _vp, _vp]
 lib.tg_clip_stats_static.restype = ctypes.c_int
 lib.tg_static_scratch_needed.argtypes = [_vp, ctypes.c_int]
@@ -213,6 +215,9 @@ class Plan:
         gp, _keep = _ptr_array(grads)
         _check(lib.tg_clip_stats(self._h, len(grads), gp, float(c), _ptr(tau), _ptr(s_local),
                                  _stream(stream)), "tg_clip_stats")
+
+    def tg_plan_set_update_kernel(self, mode: int):
+        _check(lib.tg_plan_set_update_kernel(self._h, int(mode)), "tg_plan_set_update_kernel")
 
     def tg_clip_stats_static(self, grads: Sequence, c: float, tau, s_local, stream=None):
         gp, _keep = _ptr_array(grads)

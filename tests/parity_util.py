@@ -58,7 +58,8 @@ def gpu_unpack_average(plan, codes_np, s_shared):
     return avg.cpu().numpy()
 
 
-def gpu_unpack_update(plan, codes_np, s_shared, eta, w0):
+def gpu_unpack_update(plan, codes_np, s_shared, eta, w0, kernel=0):
+    """kernel: 0 = the library's own choice by size, 1 / 2 = force one of the two update kernels"""
     pb = plan.packed_bytes
     cd = []
     for c in codes_np:
@@ -66,8 +67,12 @@ def gpu_unpack_update(plan, codes_np, s_shared, eta, w0):
         buf[:c.size] = c
         cd.append(dev(buf))
     w = dev(w0)
-    plan.tg_unpack_update(cd, dev(s_shared), eta, w)
-    torch.cuda.synchronize()
+    plan.tg_plan_set_update_kernel(kernel)
+    try:
+        plan.tg_unpack_update(cd, dev(s_shared), eta, w)
+        torch.cuda.synchronize()
+    finally:
+        plan.tg_plan_set_update_kernel(0)
     return w.cpu().numpy()
 
 
@@ -192,8 +197,10 @@ def full_parity(oracle, binding, off, grads_np, c=2.5, seed=0, step=0, worker_ba
         # the fused update line of Algorithm 1 from the same codes
         w0 = (np.random.default_rng(n + W).normal(size=n) * 0.05).astype(np.float32)
         eta = 0.125 if n % 2 else 0.01
-        assert_update_close(gpu_unpack_update(plan, o_codes, o_s, eta, w0),
-                            oracle.unpack_update(o_codes, off, o_s, eta, w0), w0, o_avg)
+        o_upd = oracle.unpack_update(o_codes, off, o_s, eta, w0)
+        upd = [gpu_unpack_update(plan, o_codes, o_s, eta, w0, kernel=k) for k in (1, 2)]
+        assert_update_close(upd[0], o_upd, w0, o_avg)
+        assert np.array_equal(upd[0], upd[1]), "the two update kernels must agree bit for bit"
         return dict(tau=o_tau, s_local=o_sloc, s_shared=o_s, codes=o_codes, avg=o_avg)
     finally:
         plan.close()

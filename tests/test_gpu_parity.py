@@ -224,11 +224,12 @@ def test_unpack_update_arbitrary_bytes_and_rates(oracle, binding):
         w0 = rng.normal(size=n).astype(np.float32)
         plan = binding.Plan(off, W)
         try:
-            got = gpu_unpack_update(plan, codes, s, eta, w0)
-            assert_update_close(got, oracle.unpack_update(codes, off, s, eta, w0), w0,
-                                oracle.unpack_average(codes, off, s))
-            if eta == 0.0:
-                assert np.array_equal(got, w0)
+            for kernel in (0, 1, 2):
+                got = gpu_unpack_update(plan, codes, s, eta, w0, kernel=kernel)
+                assert_update_close(got, oracle.unpack_update(codes, off, s, eta, w0), w0,
+                                    oracle.unpack_average(codes, off, s))
+                if eta == 0.0:
+                    assert np.array_equal(got, w0)
         finally:
             plan.close()
 
@@ -372,12 +373,18 @@ def test_momentum_update(oracle, binding):
                 buf = np.zeros(plan.packed_bytes, np.uint8)
                 buf[:c.size] = c
                 cd.append(dev(buf))
-            v, w = dev(v0), dev(w0)
-            plan.tg_unpack_update_momentum(cd, dev(s), eta, mu, v, w)
-            torch.cuda.synchronize()
             v_want, w_want = oracle.unpack_update_momentum(codes, off, s, eta, mu, v0, w0)
             avg = oracle.unpack_average(codes, off, s)
-            vg, wg = v.cpu().numpy(), w.cpu().numpy()
+            both = []
+            for kernel in (2, 1):                      # a wave per quarter tile, then the cooperative kernel
+                v, w = dev(v0), dev(w0)
+                plan.tg_plan_set_update_kernel(kernel)
+                plan.tg_unpack_update_momentum(cd, dev(s), eta, mu, v, w)
+                torch.cuda.synchronize()
+                plan.tg_plan_set_update_kernel(0)
+                both.append((v.cpu().numpy(), w.cpu().numpy()))
+            assert np.array_equal(both[0][0], both[1][0]) and np.array_equal(both[0][1], both[1][1])
+            vg, wg = both[1]
             # v' = mu v + avg: within 1e-6 of the larger term; w' = w - eta v': likewise
             v64 = v_want.astype(np.float64)
             sc_v = np.maximum(np.abs(mu * v0.astype(np.float64)), np.abs(avg.astype(np.float64)))

@@ -11,9 +11,13 @@
 //           dword written per 16 floats read (to thin): the traffic shape of tg_ternarize_pack, with the
 //           encoder's cache policy for a code stream of that size;
 //           5 the decoder's write pattern: workgroups of four waves own four tiles and write each
-//           tile together, a wave's four stores 4 KiB apart (non-temporal)
-//     src   dev [n] fp32 (kinds 0, 1, 3, 4), dst dev [n] fp32 (written by kinds 2, 3, 5; kinds 0, 1, 4
-//           may write dst[0]), thin dev [n/16] uint32 (kind 4); n a multiple of 4096; 16-byte aligned
+//           tile together, a wave's four stores 4 KiB apart (non-temporal);
+//           6 write with ONE 1 KiB store per wave (sc1), 7 copy with one 1 KiB load and one 1 KiB store
+//           per wave (nt load, sc1 + nt store): the shape of the fused-update kernel for large models;
+//           8 kind 4 with the thin stream redirected into one 64 KiB region that stays in L2: the same
+//           instructions without the write traffic to HBM
+//     src   dev [n] fp32 (kinds 0, 1, 3, 4, 7, 8), dst dev [n] fp32 (written by kinds 2, 3, 5, 6, 7; kinds
+//           0, 1, 4, 8 may write dst[0]), thin dev [n/16] uint32 (kinds 4, 8); n a multiple of 4096; 16-byte aligned
 //     returns 0, or -1 (bad argument), -2 (alignment), -4 (launch failed)
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -25,7 +29,7 @@ namespace {
 using namespace tg;
 
 enum { PROBE_READ = 0, PROBE_READ_NT = 1, PROBE_WRITE_NT = 2, PROBE_COPY_NT = 3, PROBE_READ_THIN_WRITE = 4,
-       PROBE_WRITE_NT_COOP = 5 };
+       PROBE_WRITE_NT_COOP = 5, PROBE_WRITE_ONE = 6, PROBE_COPY_ONE = 7, PROBE_READ_THIN_L2 = 8 };
 
 struct ProbeArgs {
     const float* src;     // [n_tiles * 1024]
@@ -65,6 +69,14 @@ __global__ void __launch_bounds__(kBlock) probe_kernel(const ProbeArgs p) {
         for (int k = 0; k < 4; ++k) store_stream(p.dst + (tile0 + k) * kWaveTile + 256 * wave + 4 * lane, v[k]);
         return;
     }
+    if (KIND == PROBE_READ_THIN_L2) {
+        uint32_t y = 0;
+#pragma unroll
+        for (int k = 0; k < 4; ++k)
+            y ^= __float_as_uint(v[k].x) ^ __float_as_uint(v[k].y) ^ __float_as_uint(v[k].z) ^ __float_as_uint(v[k].w);
+        p.thin[(wt & 255) * kWave + lane] = y;               // always the same 64 KiB
+        return;
+    }
     // the loads must be consumed: fold them into one word
     uint32_t x = 0;
 #pragma unroll
@@ -77,15 +89,29 @@ __global__ void __launch_bounds__(kBlock) probe_kernel(const ProbeArgs p) {
     }
 }
 
+// one 1 KiB access per stream and wave: a wave per 256 floats
+template <int KIND>
+__global__ void __launch_bounds__(kBlock) probe_one_kernel(const ProbeArgs p) {
+    const int lane = threadIdx.x & (kWave - 1);
+    const int64_t q = (int64_t)blockIdx.x * (kBlock / kWave) + (threadIdx.x >> 6);       // quarter tile
+    if (q >= 4 * p.n_tiles) return;
+    const int64_t e = q * 256 + 4 * lane;
+    float4 v = make_float4(1.0f, 2.0f, 3.0f, 0.0f);
+    if (KIND == PROBE_COPY_ONE) v = load_stream(p.src + e);
+    store_through4<KIND == PROBE_COPY_ONE>(p.dst + e, v);
+}
+
 bool aligned(const void* p, uintptr_t a) { return ((uintptr_t)p & (a - 1)) == 0; }
 
 }  // namespace
 
 extern "C" int bench_probe(int kind, const float* src, float* dst, uint32_t* thin, int64_t n, void* stream) {
     constexpr int64_t kGroup = (int64_t)kWaveTile * (kBlock / kWave);      // 4096 floats per workgroup
-    if (kind < PROBE_READ || kind > PROBE_WRITE_NT_COOP || n < kGroup || n % kGroup != 0) return -1;
-    const bool reads = kind != PROBE_WRITE_NT && kind != PROBE_WRITE_NT_COOP;
-    if ((reads && src == nullptr) || dst == nullptr || (kind == PROBE_READ_THIN_WRITE && thin == nullptr)) return -1;
+    if (kind < PROBE_READ || kind > PROBE_READ_THIN_L2 || n < kGroup || n % kGroup != 0) return -1;
+    const bool reads = kind != PROBE_WRITE_NT && kind != PROBE_WRITE_NT_COOP && kind != PROBE_WRITE_ONE;
+    const bool thins = kind == PROBE_READ_THIN_WRITE || kind == PROBE_READ_THIN_L2;
+    if ((reads && src == nullptr) || dst == nullptr || (thins && thin == nullptr)) return -1;
+    if (thins && n / 16 < 256 * kWave) return -1;              // kind 8 writes the first 64 KiB of thin
     if ((reads && !aligned(src, 16)) || !aligned(dst, 16) || (thin != nullptr && !aligned(thin, 4))) return -2;
     const ProbeArgs a{src, dst, thin, n / kWaveTile};
     const int64_t blocks = a.n_tiles / (kBlock / kWave);
@@ -102,7 +128,10 @@ extern "C" int bench_probe(int kind, const float* src, float* dst, uint32_t* thi
             if (n / 4 > kCodeStreamNtFrom) hipLaunchKernelGGL((probe_kernel<PROBE_READ_THIN_WRITE, true>), grid, block, 0, s, a);
             else hipLaunchKernelGGL((probe_kernel<PROBE_READ_THIN_WRITE, false>), grid, block, 0, s, a);
             break;
-        default: hipLaunchKernelGGL(probe_kernel<PROBE_WRITE_NT_COOP>, grid, block, 0, s, a); break;
+        case PROBE_WRITE_NT_COOP: hipLaunchKernelGGL(probe_kernel<PROBE_WRITE_NT_COOP>, grid, block, 0, s, a); break;
+        case PROBE_WRITE_ONE: hipLaunchKernelGGL(probe_one_kernel<PROBE_WRITE_ONE>, dim3((unsigned)a.n_tiles), block, 0, s, a); break;
+        case PROBE_COPY_ONE: hipLaunchKernelGGL(probe_one_kernel<PROBE_COPY_ONE>, dim3((unsigned)a.n_tiles), block, 0, s, a); break;
+        default: hipLaunchKernelGGL(probe_kernel<PROBE_READ_THIN_L2>, grid, block, 0, s, a); break;
     }
     return hipGetLastError() == hipSuccess ? 0 : -4;
 }

@@ -681,7 +681,10 @@ tg_status tg_average_float(int n_workers, int64_t n, const float* const* grads, 
     int64_t blocks = (threads + tg::kBlock - 1) / tg::kBlock;
     if (blocks < 1) blocks = 1;
     if (blocks > 0x7FFFFFFF) return TG_ERR_INVALID_ARG;
-    hipLaunchKernelGGL(tg::average_float_kernel, dim3((unsigned)blocks), dim3(tg::kBlock), 0, (hipStream_t)stream, a);
+    if (n * (int64_t)sizeof(float) > tg::kCodeStreamNtFrom)
+        hipLaunchKernelGGL(tg::average_float_kernel<true>, dim3((unsigned)blocks), dim3(tg::kBlock), 0, (hipStream_t)stream, a);
+    else
+        hipLaunchKernelGGL(tg::average_float_kernel<false>, dim3((unsigned)blocks), dim3(tg::kBlock), 0, (hipStream_t)stream, a);
     if (!hip_ok(hipGetLastError())) return TG_ERR_HIP;
     return TG_OK;
 }

@@ -82,6 +82,16 @@ __device__ __forceinline__ void store_stream(float* p, const float4 v) {
     __builtin_nontemporal_store(t, reinterpret_cast<f32x4*>(p));
 }
 
+// 128-bit store with sc1, and nt on top for outputs too large for the memory-side cache (the rule of the
+// code stream below, for the same reasons): what the plain average of float layers writes.  Measured
+// against a non-temporal store alone: 6 - 8 % faster on 240 MB of output, equal to 2 % faster on 4 GB.
+template <bool NT>
+__device__ __forceinline__ void store_through4(float* p, const float4 v) {
+    const f32x4 t = {v.x, v.y, v.z, v.w};
+    if (NT) asm volatile("global_store_dwordx4 %0, %1, off sc1 nt" ::"v"(p), "v"(t) : "memory");
+    else asm volatile("global_store_dwordx4 %0, %1, off sc1" ::"v"(p), "v"(t) : "memory");
+}
+
 // Dword store of the thin code stream that accompanies the gradient read.  Always with the sc1
 // cache-policy bit (4 % faster for the encoder than a plain store); with nt on top when the code
 // buffers of a launch are too large to stay in the 256 MB memory-side cache.  Measured with 8 workers

@@ -22,6 +22,7 @@ __device__ __forceinline__ void average_float_one(const FloatAvgArgs& p, const i
     p.avg[e] = (float)(s / dW);
 }
 
+template <bool NT_OUT>
 __global__ void __launch_bounds__(kBlock) average_float_kernel(const FloatAvgArgs p) {
     const int64_t i = p.head + ((int64_t)blockIdx.x * kBlock + threadIdx.x) * 4;
     const double dW = (double)p.n_workers;
@@ -49,7 +50,7 @@ __global__ void __launch_bounds__(kBlock) average_float_kernel(const FloatAvgArg
         }
         const float4 o = make_float4((float)(s0 / dW), (float)(s1 / dW),
                                      (float)(s2 / dW), (float)(s3 / dW));
-        store_stream(p.avg + i, o);
+        store_through4<NT_OUT>(p.avg + i, o);
     } else {
         for (int64_t e = i; e < p.n; ++e) average_float_one(p, e, dW);
     }

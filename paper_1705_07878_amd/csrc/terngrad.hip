@@ -170,17 +170,12 @@ struct tg_plan {
 
 static int64_t sum_bytes(const tg_plan* p, int bits) { return ((p->n * bits + 7) / 8 + 15) / 16 * 16; }
 
-// store policy and tile spreading of the decoders' float4 sinks (measured best on 4 GB outputs)
+// store policy of the decoders' float4 sinks (non-temporal: measured best at every size)
 constexpr int kSinkPolicy = tg::ST_NT;
-constexpr int kSinkTileShift = 0;
 
 template <int SRC, int DST, int BITS = 0>
-static tg_status launch_unpack(tg::UnpackArgs& a, void* stream) {
-    constexpr bool scaling = DST == tg::DST_AVG || DST == tg::DST_UPDATE || DST == tg::DST_MOMENTUM;
-    a.tile_shift = scaling ? kSinkTileShift : 0;
-    // whole groups of 2^shift workgroups, each group covering 4 * 2^shift consecutive tiles
-    const int64_t per_group = (int64_t)tg::kTilesPerBlock << a.tile_shift;
-    const int64_t blocks = ((a.n_wave_tiles + per_group - 1) / per_group) << a.tile_shift;
+static tg_status launch_unpack(const tg::UnpackArgs& a, void* stream) {
+    const int64_t blocks = (a.n_wave_tiles + tg::kTilesPerBlock - 1) / tg::kTilesPerBlock;
     hipLaunchKernelGGL((tg::unpack_average_kernel<kSinkPolicy, SRC, DST, BITS>), dim3((unsigned)blocks), dim3(tg::kBlock), 0,
                        (hipStream_t)stream, a);
     if (!hip_ok(hipGetLastError())) return TG_ERR_HIP;
@@ -197,7 +192,6 @@ template <int DST>
 static tg_status launch_update(tg::UnpackArgs& a, int mode, void* stream) {
     const bool quarter = mode == 2 || (mode == 0 && a.n >= kQuarterFromElements);
     if (!quarter) return launch_unpack<tg::SRC_CODES, DST>(a, stream);
-    a.tile_shift = 0;
     const int64_t blocks = a.n_wave_tiles;                 // four quarter tiles = four waves per workgroup
     hipLaunchKernelGGL((tg::unpack_quarter_kernel<kSinkPolicy, DST>), dim3((unsigned)blocks), dim3(tg::kBlock), 0,
                        (hipStream_t)stream, a);

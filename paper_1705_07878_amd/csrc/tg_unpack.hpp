@@ -36,7 +36,6 @@ struct UnpackArgs {
     int64_t packed_bytes;
     int32_t n_layers;
     int32_t n_workers;
-    int32_t tile_shift;         // log2 of the distance, in tiles, between the tiles of one workgroup (see TileMap)
 };
 
 struct Nib {
@@ -84,30 +83,26 @@ __device__ __forceinline__ float4 scale4(const uint32_t d, const float sc) {
     return o;
 }
 
-enum { ST_PLAIN = 0, ST_NT = 1, ST_SC1 = 2, ST_SC0SC1 = 3 };     // cache policy of the float4 stores
+// Cache policy of the float4 stores of the scaling sinks.  Non-temporal is what the library uses: on
+// 10^9 elements x 8 workers the decoder takes 0.964 ms with nt, 1.00 ms with sc1 or sc0 sc1, 1.01 - 1.03 ms
+// with plain stores; on the AlexNet- and VGG-A-shaped sizes 84 - 85 % of the HBM peak against 73 - 76 %.
+// (The codes themselves are read with plain loads: non-temporal ones made the decoder 1 - 5 % slower
+// inside the step, where the end of what the encoder just wrote is still cached.)
+enum { ST_PLAIN = 0, ST_NT = 1 };
 
 template <int POL>
 __device__ __forceinline__ void store4(float* dst, const float4 v) {
-    const f32x4 t = {v.x, v.y, v.z, v.w};
     if (POL == ST_NT) store_stream(dst, v);
-    else if (POL == ST_SC1) asm volatile("global_store_dwordx4 %0, %1, off sc1" ::"v"(dst), "v"(t) : "memory");
-    else if (POL == ST_SC0SC1) asm volatile("global_store_dwordx4 %0, %1, off sc0 sc1" ::"v"(dst), "v"(t) : "memory");
     else *reinterpret_cast<float4*>(dst) = v;
 }
 
-// Which tiles a workgroup owns.  Its j-th tile is base + (j << shift): consecutive tiles for shift 0;
-// for shift > 0 the workgroups of a group of 2^shift share 4 * 2^shift consecutive tiles, workgroup r
-// of the group taking the tiles r, r + 2^shift, r + 2 * 2^shift, r + 3 * 2^shift of them, so that the
-// stores a wave issues one after the other lie 2^shift tiles (4 KiB each) apart.
+// Which tiles a workgroup owns: consecutive ones from `base` on.  (Spreading them 16 to 1024 tiles apart,
+// so that the stores a wave issues one after the other lie far from each other, helps a bare write
+// pattern but not the decoders: 0.985 - 1.06 ms against 0.964 ms on 10^9 elements.)
 struct TileMap {
     int64_t base;
-    int shift;
-    __device__ __forceinline__ int64_t at(const int j) const { return base + ((int64_t)j << shift); }
+    __device__ __forceinline__ int64_t at(const int j) const { return base + j; }
 };
-__device__ __forceinline__ TileMap tile_map(const int64_t block, const int shift, const int tiles_per_block) {
-    const int64_t group = block >> shift, r = block & (((int64_t)1 << shift) - 1);
-    return TileMap{((group * tiles_per_block) << shift) + r, shift};
-}
 
 // w - eta * avg, one rounding
 __device__ __forceinline__ float4 apply4(const float4 w, const float4 a, const float eta) {
@@ -328,7 +323,7 @@ struct Emit {
     }
 };
 
-// A workgroup owns 4 tiles (see TileMap).  Wave j sums the codes of its j-th tile (one short-lived pass,
+// A workgroup owns 4 consecutive tiles.  Wave j sums the codes of its j-th tile (one short-lived pass,
 // every table lookup a scalar load); the scaling sinks then write the tiles together (see Emit).
 template <int POL, int SRC, int DST, int BITS = 0>
 __global__ void __launch_bounds__(kBlock) unpack_average_kernel(const UnpackArgs p) {
@@ -336,7 +331,7 @@ __global__ void __launch_bounds__(kBlock) unpack_average_kernel(const UnpackArgs
 
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = wave_uniform(threadIdx.x >> 6);
-    const TileMap tm = tile_map(blockIdx.x, p.tile_shift, kTilesPerBlock);
+    const TileMap tm = {(int64_t)blockIdx.x * kTilesPerBlock};
     const int64_t wt = tm.at(wave);
     const bool valid = wt < p.n_wave_tiles;
     const int64_t e0 = wt * kWaveTile;
@@ -441,7 +436,7 @@ __global__ void __launch_bounds__(kBlock) unpack_quarter_kernel(const UnpackArgs
     const int64_t tile = gq >> 2;
     const int qd = (int)(gq & 3);
     if (tile >= p.n_wave_tiles) return;
-    const TileMap tm = {tile, 0};
+    const TileMap tm = {tile};
     Emit<POL, DST, 4, 1> emit;                  // one step: quarter qd of the tile
     emit.prefetch(p, tm, qd, lane);
 
@@ -486,8 +481,7 @@ __global__ void __launch_bounds__(kBase3Block) unpack_average_base3_kernel(const
     const int W = p.n_workers;
     const int64_t tile0 = (int64_t)blockIdx.x * kBase3Waves;
 
-    // the five tiles of a workgroup are those of its 1024 consecutive code bytes: no spreading
-    const TileMap tm = {tile0, 0};
+    const TileMap tm = {tile0};
     Emit<POL, DST, kBase3Waves, kBase3Waves> emit;
     emit.prefetch(p, tm, wave, lane);
 

@@ -275,7 +275,10 @@ tg_status tg_unpack_average_base3(tg_plan* plan, int n_workers, const uint8_t* c
  * layer; its gradients travel as fp32 and are averaged as such:
  *   avg[e] = (float)( (sum_w (double)grads[w][e]) / n_workers ),  e in [0, n)
  * (fp64 sum in worker order, one rounding).  Needs no plan: the caller builds the plan over the
- * ternarized layers only and hands the float layers' slice of each flat buffer to this call.
+ * ternarized layers only and hands the float layers' slice of each flat buffer to this call.  A float
+ * layer in the middle of the buffer is handled the same way with two plans, one over the layers before
+ * it and one over the layers after it, both called on the same buffers at their offsets; the slice must
+ * then begin and end at a multiple of four elements (the alignment the plans' calls require).
  *   grads  host array of n_workers dev pointers, each to n fp32
  *   avg    dev [n] fp32 out
  * The pointers need only be float addresses, but all of them (avg included) must be congruent

@@ -294,6 +294,43 @@ def test_last_layer_in_float(oracle, binding):
     plan.close()
 
 
+def test_float_layer_in_the_middle(oracle, binding):
+    """A layer kept in fp32 anywhere in the flat buffer (Section 4.2 generalised): a plan over the
+    layers before it, a plan over the layers after it (on the same buffers, offset), and the float call
+    on the slice in between.  The only condition is the ABI's alignment: the slice begins and ends at a
+    multiple of four elements.  Every element of the average is written by exactly one of the three."""
+    rng = np.random.default_rng(29)
+    sizes = [2400, 96, 51_204, 40_000, 100_001, 10, 4097]            # layer 3 stays in fp32
+    off = _off(sizes)
+    W, n, a, b = 3, int(off[-1]), int(off[3]), int(off[4])
+    assert a % 4 == 0 and b % 4 == 0
+    grads = _grads(rng, off, W)
+    gd = [dev(g) for g in grads]
+    avg = torch.full((n,), float("nan"), dtype=torch.float32, device="cuda")
+    parts = ((0, a, off[:4]), (b, n, off[4:] - b))
+    want = np.empty(n, np.float32)
+    for lo, hi, off_p in parts:
+        r = full_parity(oracle, binding, off_p, [g[lo:hi] for g in grads], step=7, worker_base=2)
+        want[lo:hi] = r["avg"]
+        plan = binding.Plan(off_p, W)
+        try:
+            sl = [g[lo:hi] for g in gd]
+            tau, s_local = gpu_clip_stats(plan, sl, 2.5)
+            s_shared = gpu_share(plan, s_local)
+            assert np.array_equal(s_shared, r["s_shared"]) and np.array_equal(tau, r["tau"])
+            codes = gpu_ternarize(plan, sl, tau, s_shared, 0, 7, worker_base=2)
+            cd = [dev(c) for c in codes]
+            plan.tg_unpack_average(cd, dev(s_shared), avg[lo:hi])
+        finally:
+            plan.close()
+    binding.tg_average_float([g[a:b] for g in gd], b - a, avg[a:b])
+    torch.cuda.synchronize()
+    want[a:b] = oracle.average_float([g[a:b] for g in grads])
+    got = avg.cpu().numpy()
+    assert np.array_equal(got[a:b], want[a:b])
+    assert_avg_close(np.concatenate([got[:a], got[b:]]), np.concatenate([want[:a], want[b:]]))
+
+
 @pytest.mark.parametrize("W,bits", [(1, 4), (2, 4), (4, 4), (7, 4), (4, 8), (8, 8), (11, 8), (64, 8),
                                     (1, 2), (2, 3), (3, 3), (8, 5), (15, 5), (16, 6), (31, 6), (33, 7), (63, 7), (3, 5), (2, 6)])
 def test_sum_pack_and_decode_sum(oracle, binding, W, bits):

@@ -31,7 +31,7 @@ def test_every_declared_symbol_is_exported(binding):
 
 def test_strerror_and_status_values(binding):
     assert binding.tg_strerror(0) == "ok"
-    for st in (-1, -2, -3, -4, -5):
+    for st in (-1, -2, -3, -4, -5, -6):
         assert binding.tg_strerror(st) not in ("ok", "unknown status")
     assert binding.tg_strerror(-99) == "unknown status"
     hdr = open(os.path.join(ROOT, "include", "terngrad.h")).read()
@@ -64,6 +64,9 @@ def test_null_plan_is_rejected(binding):
     assert binding.lib.tg_num_elements(None) == -1
     assert binding.lib.tg_packed_bytes(None) == -1
     assert binding.lib.tg_clip_stats(None, 1, None, 2.5, None, None, None) == binding.TG_ERR_INVALID_ARG
+    assert binding.lib.tg_clip_stats_static(None, 1, None, 2.5, None, None, None) == binding.TG_ERR_INVALID_ARG
+    assert binding.lib.tg_static_scratch_needed(None, 1) == -1
+    assert binding.lib.tg_plan_set_update_kernel(None, 0) == binding.TG_ERR_INVALID_ARG
     assert binding.lib.tg_share_scalers(None, 1, None, None, None) == binding.TG_ERR_INVALID_ARG
     assert binding.lib.tg_ternarize_pack(None, 1, 0, None, None, None, 0, 0, None, None) == binding.TG_ERR_INVALID_ARG
     assert binding.lib.tg_unpack_average(None, 1, None, None, None, None) == binding.TG_ERR_INVALID_ARG

@@ -127,9 +127,11 @@ tg_status tg_describe_tables(int64_t n_layers, const int64_t* offsets, int max_w
  *            (the "TernGrad-noclip" row of Table 2): tau = +inf, s_local = max|g|
  *   tau      dev [n_workers][L] out: c * sigma of each layer of each worker
  *   s_local  dev [n_workers][L] out: min(max|g|, tau)
- * Sums are accumulated in fp64 about a per-layer pivot, in a fixed order:
- * results are identical from run to run.  An empty layer gets tau = 0 (or
- * +inf without clipping) and s_local = 0. */
+ * Sums of (g - K) and (g - K)^2 are accumulated in fp64 about the pivot K = first element of the
+ * layer, in a fixed order: results are identical from run to run, exact for a constant layer, and
+ * within 1e-7 relative of a two-pass fp64 computation whenever sigma >= 1e-3 |mean - K| (relative
+ * error about 1e-14 (1 + (mean - K)^2 / sigma^2)).  An empty layer gets tau = 0 (or +inf without
+ * clipping) and s_local = 0. */
 tg_status tg_clip_stats(tg_plan* plan, int n_workers, const float* const* grads, float c,
                         float* tau, float* s_local, void* stream);
 

@@ -249,6 +249,20 @@ def measure(torch, np, binding, workloads, key, steps, warmup, extras):
     torch.cuda.synchronize()
     ms_per_step = (time.perf_counter() - t0) * 1e3 / steps
 
+    # per-call timing with events on the launch stream, over K more steps (before the graph below is
+    # captured: host-side work around a capture has been seen to stall a later launch for milliseconds,
+    # which an event pair around a 20 us kernel would count)
+    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(5)] for _ in range(steps)]
+    for t in range(steps):
+        step(t, evs[t])
+    torch.cuda.synchronize()
+    names = ["clip_stats", "share_scalers", "ternarize_pack", "unpack_average"]
+    samples = {nm: np.array([e[i].elapsed_time(e[i + 1]) for e in evs]) for i, nm in enumerate(names)}
+    call_ms = {nm: float(samples[nm].mean()) for nm in names}
+    # an event pair also counts any time the host took to issue the call behind it: the median is shown
+    # beside the mean so that one stalled launch among K (seen after large frees) is recognisable
+    call_median_ms = {nm: float(np.median(samples[nm])) for nm in names}
+
     # the same step recorded once into a HIP graph and replayed (the iteration counter lives in device
     # memory and is advanced by the graph's last node): what a launch-bound caller would do
     step_dev = torch.zeros((1,), dtype=torch.int32, device="cuda")
@@ -271,21 +285,12 @@ def measure(torch, np, binding, workloads, key, steps, warmup, extras):
     ms_per_step_graph = (time.perf_counter() - t0) * 1e3 / steps
     del graph
 
-    # per-call timing with events on the launch stream, over K more steps (one untimed step first:
-    # the first launch after the graph's memory is released can stall for milliseconds)
-    step(0)
-    torch.cuda.synchronize()
-    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(5)] for _ in range(steps)]
-    for t in range(steps):
-        step(t, evs[t])
-    torch.cuda.synchronize()
-    names = ["clip_stats", "share_scalers", "ternarize_pack", "unpack_average"]
-    call_ms = {nm: float(np.mean([e[i].elapsed_time(e[i + 1]) for e in evs])) for i, nm in enumerate(names)}
-
     in_bytes = W * n * 4.0
     alg_bytes = {"clip_stats": W * n * 4.0, "ternarize_pack": W * n * 4.25,
                  "unpack_average": n * (4.0 + 0.25 * W)}
     kern = {nm: _rate(alg_bytes[nm], call_ms[nm]) for nm in ("clip_stats", "ternarize_pack", "unpack_average")}
+    for nm in kern:
+        kern[nm]["median_ms"] = round(call_median_ms[nm], 4)
     kern["ternarize_pack"]["fp32_in_GBps"] = round(in_bytes / (call_ms["ternarize_pack"] * 1e-3) / 1e9, 1)
     kern["share_scalers"] = {"ms": round(call_ms["share_scalers"], 4)}
     rooflines = {
@@ -408,6 +413,9 @@ def main():
     # the other target configurations, same run, same measurement (the four calls only)
     others = {}
     for key in [k for k in args.also.split(",") if k and k != args.workload]:
+        # let the driver finish releasing the previous workload's memory before anything is timed
+        torch.cuda.synchronize()
+        time.sleep(0.5)
         res, state = measure(torch, np, binding, workloads, key, args.steps, args.warmup, extras=False)
         del state
         torch.cuda.empty_cache()

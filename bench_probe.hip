@@ -1,7 +1,8 @@
 // libbench_probe.so -- a measurement instrument of bench.py, no part of the TernGrad library.
 // Memory-system probes: the access patterns of the TernGrad kernels with the arithmetic taken out,
-// on the same launch shape (one wave per tile of 1024 floats, four 128-bit accesses per lane) and
-// through the same load / store helpers as the kernels.  They give the ceilings the real kernels are
+// on the same launch shape (one wave per tile of 1024 floats, four 128-bit accesses per lane; for the
+// encoder's pattern, kinds 4 and 8, one wave per half tile as in the encoder) and through the same
+// load / store helpers as the kernels.  They give the ceilings the real kernels are
 // compared with: what this chip sustains for a plain streaming read, write, copy, and for a read
 // accompanied by a thin write.
 //
@@ -38,7 +39,7 @@ struct ProbeArgs {
     int64_t n_tiles;
 };
 
-template <int KIND, bool NT_THIN = false>
+template <int KIND>
 __global__ void __launch_bounds__(kBlock) probe_kernel(const ProbeArgs p) {
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = wave_uniform(threadIdx.x >> 6);
@@ -69,24 +70,44 @@ __global__ void __launch_bounds__(kBlock) probe_kernel(const ProbeArgs p) {
         for (int k = 0; k < 4; ++k) store_stream(p.dst + (tile0 + k) * kWaveTile + 256 * wave + 4 * lane, v[k]);
         return;
     }
-    if (KIND == PROBE_READ_THIN_L2) {
-        uint32_t y = 0;
-#pragma unroll
-        for (int k = 0; k < 4; ++k)
-            y ^= __float_as_uint(v[k].x) ^ __float_as_uint(v[k].y) ^ __float_as_uint(v[k].z) ^ __float_as_uint(v[k].w);
-        p.thin[(wt & 255) * kWave + lane] = y;               // always the same 64 KiB
-        return;
-    }
+    // (kinds 4 and 8 have a kernel of their own, below)
     // the loads must be consumed: fold them into one word
     uint32_t x = 0;
 #pragma unroll
     for (int k = 0; k < 4; ++k)
         x ^= __float_as_uint(v[k].x) ^ __float_as_uint(v[k].y) ^ __float_as_uint(v[k].z) ^ __float_as_uint(v[k].w);
-    if (KIND == PROBE_READ_THIN_WRITE) {
-        store_through<NT_THIN>(p.thin + wt * kWave + lane, x);     // 256 contiguous bytes per wave, as the code stream
-    } else if (x == 0x7FC12345u) {
+    if (x == 0x7FC12345u) {
         p.dst[0] = 1.0f;                                     // practically never: keeps the loads alive
     }
+}
+
+// The encoder's traffic: a wave reads half a tile (two 128-bit loads per lane) and its first 32 lanes
+// store one dword each, 128 contiguous bytes of the thin stream.  The thin word of lane l < 32 is the
+// XOR of the 16 floats 16 l .. 16 l + 15 of the half tile (four lanes' loads, gathered with shuffles),
+// so that tile t's 64 thin words are those of 64 groups of 16 consecutive floats.
+template <int KIND, bool NT_THIN>
+__global__ void __launch_bounds__(kBlock) probe_thin_kernel(const ProbeArgs p) {
+    const int lane = threadIdx.x & (kWave - 1);
+    const int64_t hw = (int64_t)blockIdx.x * (kBlock / kWave) + (threadIdx.x >> 6);       // half tile
+    if (hw >= 2 * p.n_tiles) return;
+    const float* g = p.src + hw * 512 + 4 * lane;
+    uint32_t x[2];
+#pragma unroll
+    for (int k = 0; k < 2; ++k) {
+        const float4 v = load_stream(g + 256 * k);
+        x[k] = __float_as_uint(v.x) ^ __float_as_uint(v.y) ^ __float_as_uint(v.z) ^ __float_as_uint(v.w);
+    }
+    // lane l < 32: floats 16 l .. 16 l + 15 = the float4s of lanes 4 (l & 15) .. + 3 in load l >> 4
+    uint32_t y = 0;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const int from = 4 * (lane & 15) + j;
+        const uint32_t a = __shfl(x[0], from, kWave), b = __shfl(x[1], from, kWave);
+        y ^= (lane & 16) ? b : a;
+    }
+    if (lane >= 32) return;
+    if (KIND == PROBE_READ_THIN_L2) p.thin[(hw & 511) * 32 + lane] = y;          // always the same 64 KiB
+    else store_through<NT_THIN>(p.thin + hw * 32 + lane, y);
 }
 
 // one 1 KiB access per stream and wave: a wave per 256 floats
@@ -123,15 +144,17 @@ extern "C" int bench_probe(int kind, const float* src, float* dst, uint32_t* thi
         case PROBE_READ_NT: hipLaunchKernelGGL(probe_kernel<PROBE_READ_NT>, grid, block, 0, s, a); break;
         case PROBE_WRITE_NT: hipLaunchKernelGGL(probe_kernel<PROBE_WRITE_NT>, grid, block, 0, s, a); break;
         case PROBE_COPY_NT: hipLaunchKernelGGL(probe_kernel<PROBE_COPY_NT>, grid, block, 0, s, a); break;
-        case PROBE_READ_THIN_WRITE:
-            // cache policy of the thin stream by its size, as the encoder chooses it
-            if (n / 4 > kCodeStreamNtFrom) hipLaunchKernelGGL((probe_kernel<PROBE_READ_THIN_WRITE, true>), grid, block, 0, s, a);
-            else hipLaunchKernelGGL((probe_kernel<PROBE_READ_THIN_WRITE, false>), grid, block, 0, s, a);
+        case PROBE_READ_THIN_WRITE: {
+            // a wave per half tile; cache policy of the thin stream by its size, as the encoder chooses it
+            const dim3 g2((unsigned)(2 * blocks));
+            if (n / 4 > kCodeStreamNtFrom) hipLaunchKernelGGL((probe_thin_kernel<PROBE_READ_THIN_WRITE, true>), g2, block, 0, s, a);
+            else hipLaunchKernelGGL((probe_thin_kernel<PROBE_READ_THIN_WRITE, false>), g2, block, 0, s, a);
             break;
+        }
         case PROBE_WRITE_NT_COOP: hipLaunchKernelGGL(probe_kernel<PROBE_WRITE_NT_COOP>, grid, block, 0, s, a); break;
         case PROBE_WRITE_ONE: hipLaunchKernelGGL(probe_one_kernel<PROBE_WRITE_ONE>, dim3((unsigned)a.n_tiles), block, 0, s, a); break;
         case PROBE_COPY_ONE: hipLaunchKernelGGL(probe_one_kernel<PROBE_COPY_ONE>, dim3((unsigned)a.n_tiles), block, 0, s, a); break;
-        default: hipLaunchKernelGGL(probe_kernel<PROBE_READ_THIN_L2>, grid, block, 0, s, a); break;
+        default: hipLaunchKernelGGL((probe_thin_kernel<PROBE_READ_THIN_L2, false>), dim3((unsigned)(2 * blocks)), block, 0, s, a); break;
     }
     return hipGetLastError() == hipSuccess ? 0 : -4;
 }

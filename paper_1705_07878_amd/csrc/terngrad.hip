@@ -469,7 +469,8 @@ static tg_status ternarize_launch(tg_plan* p, int n_workers, uint32_t worker_bas
         if (!hip_ok(hipGetLastError())) return TG_ERR_HIP;
         return TG_OK;
     }
-    const int64_t blocks = (a.n_wave_tiles + tg::kBlock / tg::kWave - 1) / (tg::kBlock / tg::kWave);
+    // a wave per half tile: four half tiles per workgroup
+    const int64_t blocks = (2 * a.n_wave_tiles + tg::kBlock / tg::kWave - 1) / (tg::kBlock / tg::kWave);
     // cache policy of the code stream by the size of the job (see store_through)
     const dim3 grid((unsigned)blocks, (unsigned)n_workers), block(tg::kBlock);
     if (a.packed_bytes * n_workers > tg::kCodeStreamNtFrom)

@@ -1,16 +1,20 @@
 // Fused clip -> Bernoulli -> sign -> 2-bit pack (Eq. 1, 3, 5 and the 2-bit
-// encoding of Section 3.1).  One wave turns 1024 consecutive gradients into
-// 256 bytes of codes per step:
-//   * four fully coalesced 128-bit loads per lane (lane l, load k reads
-//     elements 256k + 4l .. 4l+3 of the wave tile), issued before anything that
+// encoding of Section 3.1).  The unit of all tables is the tile of 1024 consecutive
+// gradients (256 bytes of codes), four quarters of 256; a wave encodes NQ quarters:
+// half a tile in the 2-bit kernel (measured 2 - 4 % faster than a whole tile per wave
+// on every size: 5.26 against 5.35 ms on 8 x 10^9 elements, 0.672 against 0.701 ms
+// on the VGG-A shapes; a quarter per wave is slower again), a whole tile in the
+// base-3 kernel.
+//   * NQ fully coalesced 128-bit loads per lane (lane l, load k reads
+//     elements 256k + 4l .. 4l+3 of the wave's part), issued before anything that
 //     depends on the layer tables, so table and data latencies overlap;
 //   * one Philox4x32-10 block yields the 16-bit fields of 8 consecutive
-//     elements, so lanes 2j and 2j+1 each compute one block (for elements
-//     8j..8j+7 of two consecutive 256-element quarters) and swap halves over DPP;
+//     elements, so lanes 2j and 2j+1 each compute one block per pair of quarters (for
+//     elements 8j..8j+7 of two consecutive 256-element quarters) and swap halves over DPP;
 //   * per element: fp32 threshold fma, clip-min, integer compare, two
 //     funnel shifts that push the "non-zero" and "negative" bits into the byte;
-//   * the four code bytes of a lane are transposed through 256 B of LDS per
-//     wave so that every lane stores one dword and the wave 256 contiguous bytes.
+//   * the NQ code bytes of a lane are transposed through 64 NQ bytes of LDS per
+//     wave so that lanes store whole dwords and the wave 64 NQ contiguous bytes.
 #pragma once
 
 #include "tg_common.hpp"
@@ -76,10 +80,13 @@ __device__ __forceinline__ uint32_t encode4v(const float4 v, const float rf[4],
     return acc;
 }
 
-// The code bytes of one 1024-element tile: b[k] = 2-bit codes of the lane's elements
-// 256k + 4*lane .. +3 (k = 0..3), for worker index w (of this call) and wave tile wt.
+// Code bytes of NQ quarters of one 1024-element tile, starting at quarter NQ * part: b[k] = 2-bit
+// codes of the lane's elements 256 (NQ * part + k) + 4*lane .. +3, for worker index w (of this call)
+// and tile wt.
+template <int NQ = 4>
 __device__ __forceinline__ void tile_code_bytes(const TernArgs& p, const int w, const int64_t wt,
-                                                const int lane, uint32_t b[4]) {
+                                                const int lane, uint32_t b[NQ], const int part = 0) {
+    const int Q0 = NQ * part;          // first quarter of the tile this wave encodes
     const float* __restrict__ g = p.grads[w];
     const uint32_t worker = p.worker_base + (uint32_t)w;
     const int par = lane & 1;
@@ -95,16 +102,16 @@ __device__ __forceinline__ void tile_code_bytes(const TernArgs& p, const int w, 
     // wave tile (also for the few padding tiles past the end), so the layer, the fast-path flag and
     // with them tau and s are two scalar loads deep, all in flight while the random bits are computed.
     const bool inside = e0 + kWaveTile <= p.n;
-    float4 v[4];
+    float4 v[NQ];
     if (inside) {
-        const float* gp = g + e0 + 4 * lane;
+        const float* gp = g + e0 + 256 * Q0 + 4 * lane;
 #pragma unroll
-        for (int k = 0; k < 4; ++k) v[k] = load_stream(gp + 256 * k);
+        for (int k = 0; k < NQ; ++k) v[k] = load_stream(gp + 256 * k);
     } else {
         // ragged end of the buffer (or past it): missing elements read as 0, which encodes to 00
 #pragma unroll
-        for (int k = 0; k < 4; ++k) {
-            const int64_t e = e0 + 256 * k + 4 * lane;
+        for (int k = 0; k < NQ; ++k) {
+            const int64_t e = e0 + 256 * (Q0 + k) + 4 * lane;
             float t[4];
 #pragma unroll
             for (int i = 0; i < 4; ++i) t[i] = (e + i < p.n) ? g[e + i] : 0.0f;
@@ -120,10 +127,10 @@ __device__ __forceinline__ void tile_code_bytes(const TernArgs& p, const int w, 
     const float s0 = p.s_shared[l0];
 
     // Philox blocks of this tile: q0 .. q0+127; lane computes q0 + 64P + 32*par + (lane>>1)
-    float rf[4][4];                // random fields of the lane's elements, quarter k, as floats
-    const uint64_t q = (uint64_t)(e0 >> 3) + (uint32_t)(32 * par + (lane >> 1));
+    float rf[NQ][4];               // random fields of the lane's elements, quarter k, as floats
+    const uint64_t q = (uint64_t)(e0 >> 3) + (uint32_t)(32 * Q0 + 32 * par + (lane >> 1));
 #pragma unroll
-    for (int P = 0; P < 2; ++P) {
+    for (int P = 0; P < NQ / 2; ++P) {
         const uint64_t qq = q + 64 * P;
         const U4 R = philox4x32_10((uint32_t)qq, (uint32_t)(qq >> 32), worker, step, p.key0, p.key1);
         // quarter 2P: elements 8j..8j+7 belong to the even lane's block; the even lane
@@ -149,15 +156,15 @@ __device__ __forceinline__ void tile_code_bytes(const TernArgs& p, const int w, 
         const float s17 = s0 * kFieldScale;
         const float s16 = s17 * 2.0f;
 #pragma unroll
-        for (int k = 0; k < 4; ++k) b[k] = encode4(v[k], rf[k], tau, s16, s17);
+        for (int k = 0; k < NQ; ++k) b[k] = encode4(v[k], rf[k], tau, s16, s17);
     } else {
         // ---- layers change inside the tile.  The layer of an element at tile position x is
         // l0 + #{ j > l0 : off[j] - e0 <= x }: a scalar pass over the (few) boundaries inside the
         // tile per quarter (the table is read through the scalar cache; keeping all 16 positions of
         // the lane live at once would cost the common path registers).
 #pragma unroll
-        for (int k = 0; k < 4; ++k) {
-            const int x0 = 256 * k + 4 * lane;
+        for (int k = 0; k < NQ; ++k) {
+            const int x0 = 256 * (Q0 + k) + 4 * lane;
             int l[4] = {l0, l0, l0, l0};
             for (int j = l0 + 1; j < p.n_layers; ++j) {
                 const int64_t rel = p.off[j] - e0;
@@ -187,27 +194,29 @@ __device__ __forceinline__ void tile_code_bytes(const TernArgs& p, const int w, 
 
 template <bool NT_CODES>
 __global__ void __launch_bounds__(kBlock) ternarize_pack_kernel(const TernArgs p) {
-    __shared__ uint32_t lds[kBlock / kWave][kWave];   // 256 B per wave
+    __shared__ uint32_t lds[kBlock / kWave][kWave / 2];   // 128 B per wave
 
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = wave_uniform(threadIdx.x >> 6);
-    // one tile per wave: short-lived waves and a very large grid stream best here, and
+    // half a tile per wave: short-lived waves and a very large grid stream best here, and
     // without a loop every table lookup is a scalar load
-    const int64_t wt = (int64_t)blockIdx.x * (kBlock / kWave) + wave;
+    const int64_t hw = (int64_t)blockIdx.x * (kBlock / kWave) + wave;     // half tile of this wave
+    const int64_t wt = hw >> 1;
+    const int part = (int)(hw & 1);
     if (wt >= p.n_wave_tiles) return;
-    uint32_t b[4];
-    tile_code_bytes(p, blockIdx.y, wt, lane, b);
+    uint32_t b[2];
+    tile_code_bytes<2>(p, blockIdx.y, wt, lane, b, part);
 
-    // ---- transpose bytes (position 64k + lane) into dwords (position 4*lane) ----
+    // ---- transpose bytes (position 64k + lane) into dwords (position 4*lane, lanes 0..31) ----
     uint8_t* row = reinterpret_cast<uint8_t*>(lds[wave]);
 #pragma unroll
-    for (int k = 0; k < 4; ++k) row[64 * k + lane] = (uint8_t)b[k];
+    for (int k = 0; k < 2; ++k) row[64 * k + lane] = (uint8_t)b[k];
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     __builtin_amdgcn_wave_barrier();
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-    const uint32_t dw = lds[wave][lane];
-    const int64_t byte0 = (wt * kWaveTile >> 2) + 4 * lane;
-    if (byte0 < p.packed_bytes) store_through<NT_CODES>(reinterpret_cast<uint32_t*>(p.codes[blockIdx.y] + byte0), dw);
+    const uint32_t dw = lds[wave][lane & 31];
+    const int64_t byte0 = (wt * kWaveTile >> 2) + 128 * part + 4 * lane;
+    if (lane < 32 && byte0 < p.packed_bytes) store_through<NT_CODES>(reinterpret_cast<uint32_t*>(p.codes[blockIdx.y] + byte0), dw);
 }
 
 // ---- base-3 container: five ternary values per byte (1.6 bits, toward 32/log2(3)) ----

@@ -22,7 +22,7 @@ def bench():
 
 def test_probe_kernels_move_what_they_claim(bench):
     """copy reproduces the source, the two write probes fill the destination, the thin stream holds
-    the XOR of each lane's 16 words, the read probes leave the destination alone"""
+    the XOR of every 16 consecutive words, the read probes leave the destination alone"""
     n = 4096 * 80
     src = torch.randn(n, device="cuda")
     dst = torch.full((n,), -7.0, device="cuda")
@@ -50,8 +50,7 @@ def test_probe_kernels_move_what_they_claim(bench):
     assert not bool(thin[256 * 64:].any()) and bool(thin[:256 * 64].any())     # only the first 64 KiB is written
     bench.bench_probe(torch, 4, src, dst, thin, n)
     torch.cuda.synchronize()
-    w = src.cpu().numpy().view(np.uint32).reshape(-1, 4, 64, 4)          # tile, k, lane, word
-    want = np.bitwise_xor.reduce(np.bitwise_xor.reduce(w, axis=3), axis=1).reshape(-1)
+    want = np.bitwise_xor.reduce(src.cpu().numpy().view(np.uint32).reshape(-1, 16), axis=1)
     assert np.array_equal(thin.cpu().numpy().view(np.uint32), want)
     for bad in (lambda: bench.bench_probe(torch, 9, src, dst, thin, n),
                 lambda: bench.bench_probe(torch, 0, src, dst, thin, 1024),

@@ -24,6 +24,7 @@
 #include <stdint.h>
 
 #include "paper_1705_07878_amd/csrc/tg_common.hpp"
+#include "paper_1705_07878_amd/csrc/tg_ternarize.hpp"      // kEncoderXcdRun
 
 namespace {
 
@@ -88,7 +89,8 @@ __global__ void __launch_bounds__(kBlock) probe_kernel(const ProbeArgs p) {
 template <int KIND, bool NT_THIN>
 __global__ void __launch_bounds__(kBlock) probe_thin_kernel(const ProbeArgs p) {
     const int lane = threadIdx.x & (kWave - 1);
-    const int64_t hw = (int64_t)blockIdx.x * (kBlock / kWave) + (threadIdx.x >> 6);       // half tile
+    // half tile, in the encoder's XCD-aware order
+    const int64_t hw = xcd_run_index(blockIdx.x, kEncoderXcdRun) * (kBlock / kWave) + (threadIdx.x >> 6);
     if (hw >= 2 * p.n_tiles) return;
     const float* g = p.src + hw * 512 + 4 * lane;
     uint32_t x[2];
@@ -138,6 +140,9 @@ extern "C" int bench_probe(int kind, const float* src, float* dst, uint32_t* thi
     const int64_t blocks = a.n_tiles / (kBlock / kWave);
     if (blocks > 0x7FFFFFFF) return -1;
     const dim3 grid((unsigned)blocks), block(kBlock);
+    // kinds 4 and 8: a wave per half tile, whole groups of 8 XCDs x kEncoderXcdRun workgroups
+    constexpr int64_t kGroupBlocks = (int64_t)kXcds * kEncoderXcdRun;
+    const int64_t thin_blocks = (2 * blocks + kGroupBlocks - 1) / kGroupBlocks * kGroupBlocks;
     hipStream_t s = (hipStream_t)stream;
     switch (kind) {
         case PROBE_READ: hipLaunchKernelGGL(probe_kernel<PROBE_READ>, grid, block, 0, s, a); break;
@@ -146,7 +151,7 @@ extern "C" int bench_probe(int kind, const float* src, float* dst, uint32_t* thi
         case PROBE_COPY_NT: hipLaunchKernelGGL(probe_kernel<PROBE_COPY_NT>, grid, block, 0, s, a); break;
         case PROBE_READ_THIN_WRITE: {
             // a wave per half tile; cache policy of the thin stream by its size, as the encoder chooses it
-            const dim3 g2((unsigned)(2 * blocks));
+            const dim3 g2((unsigned)thin_blocks);
             if (n / 4 > kCodeStreamNtFrom) hipLaunchKernelGGL((probe_thin_kernel<PROBE_READ_THIN_WRITE, true>), g2, block, 0, s, a);
             else hipLaunchKernelGGL((probe_thin_kernel<PROBE_READ_THIN_WRITE, false>), g2, block, 0, s, a);
             break;
@@ -154,7 +159,7 @@ extern "C" int bench_probe(int kind, const float* src, float* dst, uint32_t* thi
         case PROBE_WRITE_NT_COOP: hipLaunchKernelGGL(probe_kernel<PROBE_WRITE_NT_COOP>, grid, block, 0, s, a); break;
         case PROBE_WRITE_ONE: hipLaunchKernelGGL(probe_one_kernel<PROBE_WRITE_ONE>, dim3((unsigned)a.n_tiles), block, 0, s, a); break;
         case PROBE_COPY_ONE: hipLaunchKernelGGL(probe_one_kernel<PROBE_COPY_ONE>, dim3((unsigned)a.n_tiles), block, 0, s, a); break;
-        default: hipLaunchKernelGGL((probe_thin_kernel<PROBE_READ_THIN_L2, false>), dim3((unsigned)(2 * blocks)), block, 0, s, a); break;
+        default: hipLaunchKernelGGL((probe_thin_kernel<PROBE_READ_THIN_L2, false>), dim3((unsigned)thin_blocks), block, 0, s, a); break;
     }
     return hipGetLastError() == hipSuccess ? 0 : -4;
 }

@@ -470,7 +470,10 @@ static tg_status ternarize_launch(tg_plan* p, int n_workers, uint32_t worker_bas
         return TG_OK;
     }
     // a wave per half tile: four half tiles per workgroup
-    const int64_t blocks = (2 * a.n_wave_tiles + tg::kBlock / tg::kWave - 1) / (tg::kBlock / tg::kWave);
+    int64_t blocks = (2 * a.n_wave_tiles + tg::kBlock / tg::kWave - 1) / (tg::kBlock / tg::kWave);
+    // whole groups of 8 XCDs x kEncoderXcdRun workgroups (the kernel skips what lies past the last tile)
+    constexpr int64_t group = (int64_t)tg::kXcds * tg::kEncoderXcdRun;
+    blocks = (blocks + group - 1) / group * group;
     // cache policy of the code stream by the size of the job (see store_through)
     const dim3 grid((unsigned)blocks, (unsigned)n_workers), block(tg::kBlock);
     if (a.packed_bytes * n_workers > tg::kCodeStreamNtFrom)

@@ -112,6 +112,16 @@ __device__ __forceinline__ uint32_t swap_adjacent(uint32_t v) {
     return (uint32_t)__builtin_amdgcn_mov_dpp((int)v, 0xB1, 0xF, 0xF, true);
 }
 
+// Workgroups are handed to the 8 XCDs (each with its own L2) round-robin by index.  This maps a
+// workgroup index to a virtual one such that every XCD works on runs of `run` consecutive virtual
+// workgroups; the grid must be a multiple of 8 * run workgroups (indices past the work are skipped by
+// the kernels' own bounds checks).
+constexpr int kXcds = 8;
+__device__ __forceinline__ int64_t xcd_run_index(const int64_t block, const int run) {
+    const int64_t xcd = block % kXcds, j = block / kXcds;
+    return ((j / run) * kXcds + xcd) * run + j % run;
+}
+
 __device__ __forceinline__ int wave_uniform(int v) { return __builtin_amdgcn_readfirstlane(v); }
 
 }  // namespace tg

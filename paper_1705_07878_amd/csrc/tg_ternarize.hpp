@@ -192,6 +192,12 @@ __device__ __forceinline__ void tile_code_bytes(const TernArgs& p, const int w, 
     }
 }
 
+// Every XCD encodes runs of 32 consecutive workgroups (64 tiles, 256 KiB of gradient): a 64-byte line of
+// the per-tile table then goes into one L2 instead of eight, and the AlexNet- and VGG-A-shaped jobs run
+// 2 - 2.5 % faster (0.154 against 0.157 ms, 0.655 against 0.672 ms; 8 x 10^9 elements unchanged).  Runs of 8
+// or 64 workgroups are 1 - 2 % slower than no remapping, 128 and 512 help one size and hurt another.
+constexpr int kEncoderXcdRun = 32;
+
 template <bool NT_CODES>
 __global__ void __launch_bounds__(kBlock) ternarize_pack_kernel(const TernArgs p) {
     __shared__ uint32_t lds[kBlock / kWave][kWave / 2];   // 128 B per wave
@@ -200,7 +206,8 @@ __global__ void __launch_bounds__(kBlock) ternarize_pack_kernel(const TernArgs p
     const int wave = wave_uniform(threadIdx.x >> 6);
     // half a tile per wave: short-lived waves and a very large grid stream best here, and
     // without a loop every table lookup is a scalar load
-    const int64_t hw = (int64_t)blockIdx.x * (kBlock / kWave) + wave;     // half tile of this wave
+    // XCD-aware order (see kEncoderXcdRun)
+    const int64_t hw = xcd_run_index(blockIdx.x, kEncoderXcdRun) * (kBlock / kWave) + wave;     // half tile of this wave
     const int64_t wt = hw >> 1;
     const int part = (int)(hw & 1);
     if (wt >= p.n_wave_tiles) return;

@@ -144,13 +144,13 @@ tg_status tg_clip_stats(tg_plan* plan, int n_workers, const float* const* grads,
  * the buffer on the plan's device was resolved in tg_plan_create).
  *   - n_workers may exceed the plan's max_workers (up to TG_MAX_WORKERS): the plan's workspace is unused.
  *   - The job must fit: tg_static_scratch_needed(plan, n_workers) <= TG_STATIC_SCRATCH_BYTES
- *     (20 bytes per reduction segment and worker; the flat 10^9-element, 8-worker job needs 2.4 MB),
+ *     (20 bytes per reduction segment and worker; the flat 10^9-element, 8-worker job needs 9.8 MB),
  *     else TG_ERR_TOO_LARGE and nothing is launched.
  *   - Every call on a GPU, from any plan, thread or stream, shares that GPU's one buffer: calls that
  *     overlap on the device race.  Order them on one stream or with events.  The buffer keeps the
  *     last call's partial sums; nothing in it has to be cleared between calls.
  *   - The current device must be the plan's device. */
-#define TG_STATIC_SCRATCH_BYTES (8 * 1024 * 1024)
+#define TG_STATIC_SCRATCH_BYTES (16 * 1024 * 1024)
 int64_t tg_static_scratch_needed(const tg_plan* plan, int n_workers); /* bytes, or -1 for bad arguments */
 tg_status tg_clip_stats_static(tg_plan* plan, int n_workers, const float* const* grads, float c,
                                float* tau, float* s_local, void* stream);

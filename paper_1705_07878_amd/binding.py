@@ -23,7 +23,7 @@ TG_ERR_TOO_MANY_WORKERS = -3
 TG_ERR_HIP = -4
 TG_ERR_ALLOC = -5
 TG_ERR_TOO_LARGE = -6
-TG_STATIC_SCRATCH_BYTES = 8 * 1024 * 1024
+TG_STATIC_SCRATCH_BYTES = 16 * 1024 * 1024
 TG_MAX_WORKERS = 64
 
 if not os.path.exists(LIB_PATH):

@@ -22,7 +22,7 @@ static_assert(TG_MAX_WORKERS == tg::kMaxWorkers, "header and kernels disagree on
 // Workspace of tg_clip_stats_static: the per-segment partial sums, in device memory that exists from
 // the moment the library is loaded (every GPU the library runs on holds its own copy until the process
 // ends).  In host code this name is only a handle for hipGetSymbolAddress, never an address.
-#define TG_STATIC_SCRATCH_BYTES_IMPL (8 * 1024 * 1024)
+#define TG_STATIC_SCRATCH_BYTES_IMPL (16 * 1024 * 1024)
 static __device__ __align__(256) unsigned char scratch[TG_STATIC_SCRATCH_BYTES_IMPL];
 static_assert(TG_STATIC_SCRATCH_BYTES_IMPL == TG_STATIC_SCRATCH_BYTES, "header and library disagree on the scratch size");
 
@@ -45,7 +45,10 @@ struct Tables {
     std::vector<int32_t> seg_layer;
     std::vector<int64_t> seg_begin, seg_end, seg_pivot;
     std::vector<int64_t> layer_seg;   // [L+1]
-    std::vector<tg::StatUnit> units;  // workgroups of the statistics pass
+    std::vector<tg::StatUnit> units;  // workgroups of the statistics pass (looping shape)
+    std::vector<tg::StatChunk> chunks;  // one-shot shape: a record per chunk ...
+    std::vector<tg::StatSeg> segs;      // ... and per segment
+    bool wide = false;
 };
 
 tg_status check_offsets(int64_t n_layers, const int64_t* off) {
@@ -63,8 +66,6 @@ void build_tables(int64_t L, const int64_t* off, int max_workers, Tables& T) {
     const int64_t tile = tg::kWaveTile;
     T.n = n;
     T.n_tiles = (n + tile - 1) / tile;
-    T.chunk = tg::stat_chunk(n * (int64_t)max_workers);
-    const int64_t n_chunks = (n + T.chunk - 1) / T.chunk;
     // One entry per wave tile: the layer of its first element, flagged when no other layer begins
     // inside the tile (elements past n belong to nobody).  The kernels read their entry before they
     // know whether the tile lies past the end, so a few padding entries follow (the code buffers are
@@ -79,25 +80,64 @@ void build_tables(int64_t L, const int64_t* off, int max_workers, Tables& T) {
     }
     for (int64_t t = T.n_tiles; t < T.n_tiles + kTilePad; ++t)
         T.tile_info[(size_t)t] = (uint32_t)(L - 1) | tg::kTileWhole;
-    T.layer_seg.assign((size_t)L + 1, 0);
-    l = 0;
-    int64_t next_layer_mark = 0;              // layers < this already have layer_seg set
-    for (int64_t c = 0; c < n_chunks; ++c) {
-        const int64_t cb = c * T.chunk;
-        const int64_t ce = (cb + T.chunk < n) ? cb + T.chunk : n;
-        int64_t pos = cb;
-        while (pos < ce) {
-            while (pos >= off[l + 1]) ++l;
-            const int64_t end = off[l + 1] < ce ? off[l + 1] : ce;
-            while (next_layer_mark <= l) T.layer_seg[(size_t)next_layer_mark++] = (int64_t)T.seg_layer.size();
-            T.seg_layer.push_back((int32_t)l);
-            T.seg_begin.push_back(pos);
-            T.seg_end.push_back(end);
-            T.seg_pivot.push_back(off[l]);
-            pos = end;
+
+    // segments = chunks cut at the layer boundaries; returns the number of chunks that hold more than
+    // one segment or are ragged
+    auto cut = [&](int64_t chunk) {
+        T.seg_layer.clear(), T.seg_begin.clear(), T.seg_end.clear(), T.seg_pivot.clear();
+        T.layer_seg.assign((size_t)L + 1, 0);
+        const int64_t n_chunks = (n + chunk - 1) / chunk;
+        int64_t lay = 0, mixed = 0;
+        int64_t next_layer_mark = 0;              // layers < this already have layer_seg set
+        for (int64_t c = 0; c < n_chunks; ++c) {
+            const int64_t cb = c * chunk;
+            const int64_t ce = (cb + chunk < n) ? cb + chunk : n;
+            int64_t pos = cb, in_chunk = 0;
+            while (pos < ce) {
+                while (pos >= off[lay + 1]) ++lay;
+                const int64_t end = off[lay + 1] < ce ? off[lay + 1] : ce;
+                while (next_layer_mark <= lay) T.layer_seg[(size_t)next_layer_mark++] = (int64_t)T.seg_layer.size();
+                T.seg_layer.push_back((int32_t)lay);
+                T.seg_begin.push_back(pos);
+                T.seg_end.push_back(end);
+                T.seg_pivot.push_back(off[lay]);
+                pos = end;
+                ++in_chunk;
+            }
+            if (in_chunk > 1 || ce - cb < chunk) ++mixed;
         }
+        while (next_layer_mark <= L) T.layer_seg[(size_t)next_layer_mark++] = (int64_t)T.seg_layer.size();
+        return mixed;
+    };
+    const int64_t total = n * (int64_t)max_workers;
+    if (total >= tg::kStatWideFrom) {
+        T.chunk = tg::kStatWideChunk;
+        const int64_t mixed = cut(T.chunk);
+        T.wide = tg::stat_wide(total, (n + T.chunk - 1) / T.chunk, mixed);
     }
-    while (next_layer_mark <= L) T.layer_seg[(size_t)next_layer_mark++] = (int64_t)T.seg_layer.size();
+    if (!T.wide) {
+        T.chunk = tg::stat_chunk(total);
+        cut(T.chunk);
+    }
+    if (T.wide) {
+        // one-shot shape: the segments of chunk c are consecutive, beginning with the first one that
+        // starts at or after c * chunk (every chunk below n holds at least one element)
+        const int64_t n_chunks = (n + T.chunk - 1) / T.chunk;
+        const int64_t n_segs = (int64_t)T.seg_layer.size();
+        T.segs.resize((size_t)n_segs);
+        T.chunks.resize((size_t)n_chunks);
+        for (int64_t i = 0; i < n_segs; ++i) {
+            T.segs[(size_t)i] = tg::StatSeg{T.seg_begin[(size_t)i], T.seg_end[(size_t)i], T.seg_pivot[(size_t)i], 0};
+            const int64_t c = T.seg_begin[(size_t)i] / T.chunk;
+            tg::StatChunk& r = T.chunks[(size_t)c];
+            if (r.nseg == 0) {
+                r.seg0 = i;
+                r.pivot = T.seg_pivot[(size_t)i];
+            }
+            ++r.nseg;
+        }
+        return;
+    }
     // workgroups: one large segment each, or up to four consecutive small ones (a wave each)
     const int64_t n_segs = (int64_t)T.seg_layer.size();
     for (int64_t i = 0; i < n_segs;) {
@@ -156,12 +196,16 @@ bool aligned(const void* p, uintptr_t a) { return ((uintptr_t)p & (a - 1)) == 0;
 struct tg_plan {
     int64_t n_layers = 0, n = 0, packed_bytes = 0, n_tiles = 0, n_segs = 0, n_units = 0;
     int max_workers = 0;
+    bool stat_wide = false;         // statistics pass in its one-shot shape (jobs of max_workers * n elements)
     int update_mode = 0;            // kernel of the fused update: 0 by size, 1 cooperative, 2 quarter tiles
     int device = -1;                // the device that was current at tg_plan_create
     void* d_scratch = nullptr;      // that device's copy of the static scratch array
     int64_t* d_off = nullptr;
     uint32_t* d_tile_info = nullptr;
     tg::StatUnit* d_units = nullptr;
+    tg::StatChunk* d_chunks = nullptr;
+    tg::StatSeg* d_segs = nullptr;
+    int64_t n_chunks = 0;
     int64_t* d_layer_seg = nullptr;
     double* d_psum = nullptr;
     double* d_psq = nullptr;
@@ -299,10 +343,12 @@ tg_status tg_plan_create(int64_t n_layers, const int64_t* offsets, int max_worke
     p->n_segs = (int64_t)T.seg_layer.size();
     p->n_units = (int64_t)T.units.size();
     p->max_workers = max_workers;
+    p->stat_wide = T.wide;
+    p->n_chunks = (int64_t)T.chunks.size();
 
     const size_t np = (size_t)p->n_segs * (size_t)max_workers;
     bool ok = upload(&p->d_off, off) && upload(&p->d_tile_info, T.tile_info) &&
-              upload(&p->d_units, T.units) &&
+              upload(&p->d_units, T.units) && upload(&p->d_chunks, T.chunks) && upload(&p->d_segs, T.segs) &&
               upload(&p->d_layer_seg, T.layer_seg) &&
               hip_ok(hipMalloc((void**)&p->d_psum, np * sizeof(double))) &&
               hip_ok(hipMalloc((void**)&p->d_psq, np * sizeof(double))) &&
@@ -318,7 +364,7 @@ tg_status tg_plan_create(int64_t n_layers, const int64_t* offsets, int max_worke
 
 tg_status tg_plan_destroy(tg_plan* p) {
     if (p == nullptr) return TG_OK;
-    void* bufs[] = {p->d_off, p->d_tile_info, p->d_units, p->d_layer_seg, p->d_psum, p->d_psq, p->d_pmax};
+    void* bufs[] = {p->d_off, p->d_tile_info, p->d_units, p->d_chunks, p->d_segs, p->d_layer_seg, p->d_psum, p->d_psq, p->d_pmax};
     bool ok = true;
     for (void* b : bufs)
         if (b != nullptr) ok = hip_ok(hipFree(b)) && ok;
@@ -347,21 +393,40 @@ static tg_status clip_stats_launch(tg_plan* p, int n_workers, const float* const
                                    float* tau, float* s_local, double* psum, double* psq, float* pmax,
                                    void* stream) {
     if (grads == nullptr || tau == nullptr || s_local == nullptr || std::isnan(c)) return TG_ERR_INVALID_ARG;
-    tg::StatsArgs a{};
+    const float* checked[TG_MAX_WORKERS];
     for (int w = 0; w < n_workers; ++w) {
         if (grads[w] == nullptr) return TG_ERR_INVALID_ARG;
         if (!aligned(grads[w], 16)) return TG_ERR_ALIGNMENT;
-        a.grads[w] = grads[w];
+        checked[w] = grads[w];
     }
     if (!aligned(tau, 4) || !aligned(s_local, 4)) return TG_ERR_ALIGNMENT;
-    a.units = p->d_units;
-    a.psum = psum;
-    a.psq = psq;
-    a.pmax = pmax;
-    a.n_segs = p->n_segs;
     hipStream_t s = (hipStream_t)stream;
-    hipLaunchKernelGGL(tg::clip_stats_partial_kernel, dim3((unsigned)p->n_units, (unsigned)n_workers),
-                       dim3(tg::kBlock), 0, s, a);
+    if (p->stat_wide) {
+        tg::StatsWideArgs a{};
+        for (int w = 0; w < n_workers; ++w) a.grads[w] = checked[w];
+        a.chunks = p->d_chunks;
+        a.segs = p->d_segs;
+        a.psum = psum;
+        a.psq = psq;
+        a.pmax = pmax;
+        a.n_segs = p->n_segs;
+        a.n_chunks = p->n_chunks;
+        a.n = p->n;
+        const int64_t per = (int64_t)tg::kXcds * tg::kStatXcdRun;
+        const int64_t blocks = (p->n_chunks + per - 1) / per * per;
+        hipLaunchKernelGGL(tg::clip_stats_wide_kernel, dim3((unsigned)blocks, (unsigned)n_workers),
+                           dim3(tg::kStatWideBlock), 0, s, a);
+    } else {
+        tg::StatsArgs a{};
+        for (int w = 0; w < n_workers; ++w) a.grads[w] = checked[w];
+        a.units = p->d_units;
+        a.psum = psum;
+        a.psq = psq;
+        a.pmax = pmax;
+        a.n_segs = p->n_segs;
+        hipLaunchKernelGGL(tg::clip_stats_partial_kernel<tg::kBlock>,
+                           dim3((unsigned)p->n_units, (unsigned)n_workers), dim3(tg::kBlock), 0, s, a);
+    }
     if (!hip_ok(hipGetLastError())) return TG_ERR_HIP;
 
     tg::StatsFinalArgs f{};

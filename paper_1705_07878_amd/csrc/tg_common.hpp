@@ -47,6 +47,14 @@ __device__ __forceinline__ float max_abs(float m, float x) {
     return r;
 }
 
+// A wave-uniform read of memory that no kernel writes while this one runs (tables, the gradients in
+// the statistics pass), through the constant address space: a scalar load, which travels beside the
+// vector loads in flight instead of queueing behind them.
+template <typename T>
+__device__ __forceinline__ T load_uniform(const T* p) {
+    return *reinterpret_cast<const __attribute__((address_space(4))) T*>((uintptr_t)p);
+}
+
 // Ten rounds over counter (c0,c1,c2,c3) under key (k0,k1).  The key schedule is
 // wave-uniform (it depends on the seed alone) and ends up in scalar registers.
 __device__ __forceinline__ U4 philox4x32_10(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3,

@@ -4,21 +4,49 @@
 // same pass.  Sums are fp64 and taken about a per-layer pivot K = first element
 // of the layer (shifted-data variance: exact for a constant layer, insensitive to
 // a large mean).  No float atomics: every statistics chunk (8192 to 65536 elements, by the size of
-// the job) is cut into segments, one per layer it touches; a
-// workgroup reduces one large segment (or four small ones, a wave each) in a fixed tree and
-// writes one partial per segment; a second small kernel folds the partials of each layer in
-// a fixed order.  Results are bit-identical from
-// run to run.
+// the job) is cut into segments, one per layer it touches; a workgroup reduces one large segment (or
+// four small ones, a wave each) in a fixed tree and writes one partial per segment; a second small
+// kernel folds the partials of each layer in a fixed order.  Results are bit-identical from run to
+// run.  Large jobs take a second shape of the first kernel (clip_stats_wide_kernel).
 #pragma once
 
 #include "tg_common.hpp"
 
 namespace tg {
 
-// elements per statistics chunk (a workgroup reduces at most one chunk): 256 threads x 8..64 float4.
-// Larger chunks amortise the per-workgroup cost, smaller ones keep enough workgroups in flight; the
-// best size grows with the total work of a call (measured: 8192 for 25 M elements over all
-// workers, 16384 - 32768 for 244 M, 65536 from 1 G on).
+// Two shapes of the statistics pass, by the total work of a call (elements of all workers):
+//   * workgroups of 256 threads that loop over a chunk of 8192 to 65536 elements (larger chunks amortise
+//     the per-workgroup cost, smaller ones keep enough workgroups in flight; measured best: 8192 for 25 M
+//     elements, 16384 - 32768 for 244 M, 65536 from 1 G on);
+//   * from kStatWideFrom elements on: workgroups of 1024 threads that read a chunk of 16384 elements in
+//     one shot (four 128-bit loads per thread, no loop), mapped to the chunks so that every XCD reads runs
+//     of kStatXcdRun consecutive chunks (1 MiB).  The bare pattern reads 8 x 10^9 elements at 92 % of the
+//     8 TB/s peak where the loop over 65536 elements reaches 87.5 % (runs of 4 / 8 / 32 chunks 90.9 / 92.2 /
+//     92.3 %, natural order 83 %; 512 threads 90 %; eight loads per thread 89 - 90 %; two 74 %: the
+//     barrier and the launch of sixteen waves then weigh more than the reading); the kernel itself gains
+//     2.5 % on 8 x 10^9 elements and 1 - 3 % on the VGG-A shapes, and loses 3 % on the AlexNet shapes
+//     (2.4 x 10^8 elements), hence the threshold.  A wave per 1 - 4 KiB with a partial of its own reads at
+//     50 - 85 %: the thin stream of partials costs what the code stream costs the encoder, so partials
+//     stay rare (one per 64 KiB).
+#ifndef TG_STAT_WIDE_FROM
+#define TG_STAT_WIDE_FROM ((int64_t)1 << 29)
+#endif
+#ifndef TG_STAT_XCD_RUN
+#define TG_STAT_XCD_RUN 16
+#endif
+constexpr int64_t kStatWideFrom = TG_STAT_WIDE_FROM;
+constexpr int kStatWideBlock = 1024;
+constexpr int kStatWideChunk = 16384;
+constexpr int kStatXcdRun = TG_STAT_XCD_RUN;
+
+// (chunks that a layer begins in take a slow path in the one-shot shape, so they have to be few: at most
+// one in kStatWideMixedPer)
+constexpr int64_t kStatWideMixedPer = 64;
+__host__ __device__ constexpr bool stat_wide(const int64_t total_elements, const int64_t n_chunks, const int64_t mixed_chunks) {
+    return total_elements >= kStatWideFrom && mixed_chunks * kStatWideMixedPer <= n_chunks;
+}
+
+// elements per statistics chunk of the looping shape (a workgroup reduces at most one chunk)
 __host__ __device__ constexpr int stat_chunk(const int64_t total_elements) {
     return total_elements < ((int64_t)1 << 26) ? 8192
          : total_elements < ((int64_t)1 << 28) ? 16384
@@ -68,14 +96,57 @@ __device__ __forceinline__ void acc_add4(Acc& a, const float4 v, const double K)
     acc_add(a, v.w, K);
 }
 
-// xor butterfly: every lane ends with the same bits (a + b == b + a at each step)
+// Sum / maximum over the 64 lanes in a fixed order, the same value in every lane: inside each row of
+// 16 lanes four data-parallel-primitive steps (swap with the neighbour, with the neighbouring pair,
+// rotate the row by 4 and by 8), then lanes 0, 16, 32, 48 are read out and folded.  (A butterfly of six
+// cross-lane exchanges through the LDS crossbar takes several times as long, and a wave that has
+// nothing left to load still holds its place on the SIMD while it reduces.)
+constexpr int kDppSwap1 = 0xB1;         // quad_perm [1,0,3,2]
+constexpr int kDppSwap2 = 0x4E;         // quad_perm [2,3,0,1]
+constexpr int kDppRowRor4 = 0x124;
+constexpr int kDppRowRor8 = 0x128;
+
+template <int CTRL>
+__device__ __forceinline__ double dpp_move(const double x) {
+    const int lo = __builtin_amdgcn_update_dpp(0, __double2loint(x), CTRL, 0xf, 0xf, true);
+    const int hi = __builtin_amdgcn_update_dpp(0, __double2hiint(x), CTRL, 0xf, 0xf, true);
+    return __hiloint2double(hi, lo);
+}
+
+template <int CTRL>
+__device__ __forceinline__ float dpp_move(const float x) {
+    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), CTRL, 0xf, 0xf, true));
+}
+
+__device__ __forceinline__ double read_lane(const double x, const int l) {
+    return __hiloint2double(__builtin_amdgcn_readlane(__double2hiint(x), l),
+                            __builtin_amdgcn_readlane(__double2loint(x), l));
+}
+
+__device__ __forceinline__ float read_lane(const float x, const int l) {
+    return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(x), l));
+}
+
+__device__ __forceinline__ double wave_sum(double x) {
+    x += dpp_move<kDppSwap1>(x);
+    x += dpp_move<kDppSwap2>(x);
+    x += dpp_move<kDppRowRor4>(x);
+    x += dpp_move<kDppRowRor8>(x);
+    return (read_lane(x, 0) + read_lane(x, 16)) + (read_lane(x, 32) + read_lane(x, 48));
+}
+
+__device__ __forceinline__ float wave_max(float x) {
+    x = fmaxf(x, dpp_move<kDppSwap1>(x));
+    x = fmaxf(x, dpp_move<kDppSwap2>(x));
+    x = fmaxf(x, dpp_move<kDppRowRor4>(x));
+    x = fmaxf(x, dpp_move<kDppRowRor8>(x));
+    return fmaxf(fmaxf(read_lane(x, 0), read_lane(x, 16)), fmaxf(read_lane(x, 32), read_lane(x, 48)));
+}
+
 __device__ __forceinline__ Acc wave_reduce(Acc a) {
-#pragma unroll
-    for (int o = 32; o >= 1; o >>= 1) {
-        a.s1 += __shfl_xor(a.s1, o, kWave);
-        a.s2 += __shfl_xor(a.s2, o, kWave);
-        a.m = fmaxf(a.m, __shfl_xor(a.m, o, kWave));
-    }
+    a.s1 = wave_sum(a.s1);
+    a.s2 = wave_sum(a.s2);
+    a.m = wave_max(a.m);
     return a;
 }
 
@@ -130,19 +201,22 @@ __device__ __forceinline__ Acc segment_sums(const float* __restrict__ g, const i
     return a;
 }
 
-// One workgroup per unit: either one large segment (a run of at most one chunk inside one layer),
-// reduced by all 256 threads, or up to four small segments, one per wave.
-__global__ void __launch_bounds__(kBlock) clip_stats_partial_kernel(const StatsArgs p) {
-    __shared__ double sh1[kBlock / kWave], sh2[kBlock / kWave];
-    __shared__ float shm[kBlock / kWave];
+// One workgroup of NT threads per unit: either one large segment (a run of at most one chunk inside
+// one layer), reduced by all threads, or up to four small segments, one per wave (of the first four).
+template <int NT>
+__global__ void __launch_bounds__(NT) clip_stats_partial_kernel(const StatsArgs p) {
+    constexpr int NW = NT / kWave;
+    __shared__ double sh1[NW], sh2[NW];
+    __shared__ float shm[NW];
 
+    const int64_t unit = blockIdx.x;
     const int w = blockIdx.y;
     const float* __restrict__ g = p.grads[w];
     const int t = threadIdx.x;
     // everything a wave needs comes from its slot of the unit record, whatever the kind of unit (the
     // host repeats a large segment in all four slots): one load, which does not wait for the branch below
     const int wave = wave_uniform(t >> 6);
-    const StatSlot& u = p.units[blockIdx.x].slot[wave];
+    const StatSlot& u = p.units[unit].slot[wave & (kBlock / kWave - 1)];
     const int64_t sg = u.seg_kind >> 3;
     const int count = (int)(u.seg_kind & 7);
     const int64_t sb = u.begin, se = u.end;
@@ -168,7 +242,7 @@ __global__ void __launch_bounds__(kBlock) clip_stats_partial_kernel(const StatsA
         return;
     }
 
-    Acc a = segment_sums(g, sb, se, K, t, kBlock);
+    Acc a = segment_sums(g, sb, se, K, t, NT);
     a = wave_reduce(a);
     if ((t & 63) == 0) {
         sh1[t >> 6] = a.s1;
@@ -180,7 +254,7 @@ __global__ void __launch_bounds__(kBlock) clip_stats_partial_kernel(const StatsA
         double s1 = sh1[0], s2 = sh2[0];
         float m = shm[0];
 #pragma unroll
-        for (int k = 1; k < kBlock / kWave; ++k) {
+        for (int k = 1; k < NW; ++k) {
             s1 += sh1[k];
             s2 += sh2[k];
             m = fmaxf(m, shm[k]);
@@ -189,6 +263,109 @@ __global__ void __launch_bounds__(kBlock) clip_stats_partial_kernel(const StatsA
         p.psum[o] = s1;
         p.psq[o] = s2;
         p.pmax[o] = m;
+    }
+}
+
+// ---- the one-shot shape for large jobs ----
+// A workgroup of 1024 threads per chunk of 16384 elements.  The address of the data follows from the
+// workgroup index alone, so the four loads of every thread are issued first; the chunk's record (which
+// segments it holds, where their layer begins) and the pivot arrive while those are in flight.  A
+// chunk inside one layer - all but a few - is then one segment and one partial; a chunk that layers
+// begin in is reduced segment by segment by the general routine (the loads issued ahead are wasted).
+struct StatChunk {
+    int64_t seg0;                   // index of the chunk's first segment
+    int64_t pivot;                  // index of the first element of that segment's layer
+    int32_t nseg;                   // segments in the chunk
+    int32_t pad0;
+    int64_t pad1;
+};
+static_assert(sizeof(StatChunk) == 32, "two records per 64-byte line");
+
+struct StatSeg {
+    int64_t begin, end;             // element range
+    int64_t pivot;                  // index of the first element of the segment's layer
+    int64_t pad;
+};
+
+struct StatsWideArgs {
+    const float* grads[kMaxWorkers];
+    const StatChunk* chunks;        // [n_chunks]
+    const StatSeg* segs;            // [n_segs]
+    double* psum;
+    double* psq;
+    float* pmax;
+    int64_t n_segs, n_chunks, n;
+};
+
+constexpr int kStatWideWaves = kStatWideBlock / kWave;
+
+// fold of the workgroup's sixteen waves in a fixed order; thread 0 writes the partial of segment sg
+__device__ __forceinline__ void wide_fold_store(const StatsWideArgs& p, Acc a, const int w, const int64_t sg,
+                                                double* sh1, double* sh2, float* shm) {
+    const int t = threadIdx.x;
+    a = wave_reduce(a);
+    if ((t & 63) == 0) {
+        sh1[t >> 6] = a.s1;
+        sh2[t >> 6] = a.s2;
+        shm[t >> 6] = a.m;
+    }
+    __syncthreads();
+    if (t == 0) {
+        double s1 = sh1[0], s2 = sh2[0];
+        float m = shm[0];
+#pragma unroll
+        for (int k = 1; k < kStatWideWaves; ++k) {
+            s1 += sh1[k];
+            s2 += sh2[k];
+            m = fmaxf(m, shm[k]);
+        }
+        const int64_t o = (int64_t)w * p.n_segs + sg;
+        p.psum[o] = s1;
+        p.psq[o] = s2;
+        p.pmax[o] = m;
+    }
+}
+
+__global__ void __launch_bounds__(kStatWideBlock) clip_stats_wide_kernel(const StatsWideArgs p) {
+    __shared__ double sh1[kStatWideWaves], sh2[kStatWideWaves];
+    __shared__ float shm[kStatWideWaves];
+
+    // chunks in the XCD-aware order (the grid is rounded up to whole runs)
+    const int64_t c = xcd_run_index(blockIdx.x, kStatXcdRun);
+    if (c >= p.n_chunks) return;
+    const int w = blockIdx.y;
+    const float* __restrict__ g = p.grads[w];
+    const int t = threadIdx.x;
+    const int64_t e0 = c * kStatWideChunk;
+    const bool full = e0 + kStatWideChunk <= p.n;
+    float4 v[4];
+    if (full) {
+        const float* gp = g + e0 + 4 * t;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) v[k] = load_stream(gp + 4 * kStatWideBlock * k);
+    }
+    // the record and the pivot are scalar loads: they arrive beside the data, not behind it
+    const StatChunk* r = p.chunks + c;
+    const int64_t seg0 = load_uniform(&r->seg0);
+    const int nseg = load_uniform(&r->nseg);
+    if (full && nseg == 1) {
+        const double K = (double)load_uniform(g + load_uniform(&r->pivot));
+        Acc a = {0.0, 0.0, 0.0f};
+#pragma unroll
+        for (int k = 0; k < 4; ++k) acc_add4(a, v[k], K);
+        wide_fold_store(p, a, w, seg0, sh1, sh2, shm);
+        return;
+    }
+    // the rare kind of chunk (the host takes this shape only when fewer than one chunk in 64 is of this
+    // kind): plain strided loads, few registers, so that the kernel as a whole stays at two workgroups per CU
+    for (int j = 0; j < nseg; ++j) {
+        const StatSeg* sg = p.segs + seg0 + j;
+        const int64_t b = load_uniform(&sg->begin), e = load_uniform(&sg->end);
+        const double K = (double)load_uniform(g + load_uniform(&sg->pivot));
+        Acc a = {0.0, 0.0, 0.0f};
+        for (int64_t i = b + t; i < e; i += kStatWideBlock) acc_add(a, g[i], K);
+        wide_fold_store(p, a, w, seg0 + j, sh1, sh2, shm);
+        __syncthreads();            // the fold has read the wave sums before the next segment overwrites them
     }
 }
 
@@ -232,10 +409,24 @@ __global__ void __launch_bounds__(kFinalBlock) clip_stats_final_kernel(const Sta
     const int64_t sb = p.layer_seg[l], se = p.layer_seg[l + 1];
     const int64_t base = (int64_t)w * p.n_segs;
     Acc a = {0.0, 0.0, 0.0f};
-    for (int64_t i = sb + t; i < se; i += kFinalBlock) {
-        a.s1 += p.psum[base + i];
-        a.s2 += p.psq[base + i];
-        a.m = fmaxf(a.m, p.pmax[base + i]);
+    // four partials per thread in flight (a long layer of a large job has tens of thousands)
+    for (int64_t i = sb + t; i < se; i += 4 * kFinalBlock) {
+        double x1[4], x2[4];
+        float xm[4];
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const int64_t j = i + k * kFinalBlock;
+            const bool have = j < se;
+            x1[k] = have ? p.psum[base + j] : 0.0;
+            x2[k] = have ? p.psq[base + j] : 0.0;
+            xm[k] = have ? p.pmax[base + j] : 0.0f;
+        }
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            a.s1 += x1[k];
+            a.s2 += x2[k];
+            a.m = fmaxf(a.m, xm[k]);
+        }
     }
     a = wave_reduce(a);
     if ((t & 63) == 0) {
@@ -259,7 +450,7 @@ __global__ void __launch_bounds__(kFinalBlock) clip_stats_final_kernel(const Sta
 
 // Many layers (fine buckets): a thread per layer.  A layer with a few partials is folded by its own
 // thread, one after the other; the layers of a wave that have more are then folded by the whole
-// wave, layer after layer (lanes strided over the partials, xor butterfly).  Which of the two a
+// wave, layer after layer (lanes strided over the partials, fixed-order wave reduction).  Which of the two a
 // layer gets depends on its number of partials alone, so the order of the additions is fixed.
 constexpr int kFinalPerThreadFrom = 1024;   // layers
 constexpr int kFinalSerial = 8;           // partials a single thread folds

@@ -118,13 +118,27 @@ def test_tables_match_brute_force(binding, sizes):
 
 
 def test_statistics_chunk_follows_the_size_of_the_job(binding):
-    # chunk = 8192 / 16384 / 32768 / 65536 elements for n * max_workers below 2^26 / 2^28 / 2^29 / beyond
+    # looping shape: chunk = 8192 / 16384 / 32768 / 65536 elements for n * max_workers below 2^26 / 2^28 / 2^29 /
+    # beyond; from 2^29 on the one-shot shape with chunks of 16384, unless layers begin in too many chunks
     for n, W, chunk in ((1000, 1, 8192), (2 ** 26 - 1, 1, 8192), (2 ** 26, 1, 16384), (2 ** 24, 4, 16384),
-                        (2 ** 24, 16, 32768), (60_965_224, 4, 16384), (132_863_336, 8, 65536), (6_296_176, 4, 8192)):
+                        (2 ** 24, 16, 32768), (60_965_224, 4, 16384), (2 ** 29 - 1, 1, 32768), (2 ** 29, 1, 16384),
+                        (132_863_336, 8, 16384), (6_296_176, 4, 8192)):
         d = binding.tg_describe_tables(np.array([0, n]), W)
         assert d["chunk_elems"] == chunk, (n, W, d["chunk_elems"])
         s = d["segments"]
         assert s.shape[0] == -(-n // chunk) and s[0, 1] == 0 and s[-1, 2] == n and np.all(s[:, 2] - s[:, 1] <= chunk)
+    # 2^23 elements x 64 workers in layers of 4096: four segments in every chunk of 16384 -> the looping shape
+    off = np.arange(0, 2 ** 23 + 1, 4096, dtype=np.int64)
+    assert binding.tg_describe_tables(off, 64)["chunk_elems"] == 65536
+    # the same size with a layer boundary in one chunk out of 64 (and a ragged last chunk): still one-shot ...
+    off = np.concatenate([np.arange(0, 2 ** 23, 64 * 16384, dtype=np.int64) + 5, [2 ** 23 + 100]])
+    off[0] = 0
+    d = binding.tg_describe_tables(off, 64)
+    assert d["chunk_elems"] == 16384 and d["segments"].shape[0] == 2 ** 23 // 16384 + 1 + 7
+    # ... and with twice as many boundaries not
+    off = np.concatenate([np.arange(0, 2 ** 23, 32 * 16384, dtype=np.int64) + 5, [2 ** 23 + 100]])
+    off[0] = 0
+    assert binding.tg_describe_tables(off, 64)["chunk_elems"] == 65536
     with pytest.raises(binding.TgError):
         binding.tg_describe_tables(np.array([0, 10]), 0)
     with pytest.raises(binding.TgError):

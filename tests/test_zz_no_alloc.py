@@ -62,8 +62,8 @@ def test_static_variant_accepts_more_workers_than_the_plan_and_rejects_what_does
         assert np.allclose(tau.cpu().numpy()[:, 0], want, rtol=1e-5)
     finally:
         plan.close()
-    # 2^19 one-element layers = 2^19 segments x 20 bytes > 8 MiB: rejected, nothing launched
-    L = 1 << 19
+    # 2^20 one-element layers = 2^20 segments x 20 bytes > 16 MiB: rejected, nothing launched
+    L = 1 << 20
     big = binding.Plan(np.arange(L + 1, dtype=np.int64), 1)
     try:
         assert big.tg_static_scratch_needed(1) == 20 * L > binding.TG_STATIC_SCRATCH_BYTES

@@ -15,12 +15,12 @@ def binding():
     return b
 
 
-def _both(binding, sizes, W, c, seed):
+def _both(binding, sizes, W, c, seed, max_workers=None):
     off = np.concatenate([[0], np.cumsum(sizes)]).astype(np.int64)
     n, L = int(off[-1]), len(sizes)
     gen = torch.Generator("cuda").manual_seed(seed)
     grads = [torch.randn(n, device="cuda", generator=gen) * 1e-3 + 1e-4 for _ in range(W)]
-    plan = binding.Plan(off, W)
+    plan = binding.Plan(off, max_workers or W)
     try:
         out = []
         for call in (plan.tg_clip_stats, plan.tg_clip_stats_static):
@@ -43,6 +43,17 @@ def test_static_scratch_variant_equals_the_plan_workspace_variant(binding):
                               ([9_000] * 7, 3, 0.0, 3)):
         (tau_a, s_a), (tau_b, s_b) = _both(binding, sizes, W, c, seed)
         assert np.isfinite(s_a).all() and not np.isnan(tau_a).any()
+        assert np.array_equal(tau_a, tau_b) and np.array_equal(s_a, s_b)
+
+
+def test_static_scratch_variant_in_the_one_shot_shape_of_large_jobs(binding):
+    # a plan for 64 workers of 8.47 M elements (2^29 elements per call and more: workgroups of 1024 threads per
+    # chunk of 16384), used by three; then a small model again
+    sizes = [3, 3_000_001, 70_000, 5_400_001, 11]
+    assert int(binding.tg_describe_tables(np.concatenate([[0], np.cumsum(sizes)]), 64)["chunk_elems"]) == 16384
+    for sz, W, mw, seed in ((sizes, 3, 64, 4), ([20_000, 1, 5_000, 300], 2, 2, 5)):
+        (tau_a, s_a), (tau_b, s_b) = _both(binding, sz, W, 2.5, seed, max_workers=mw)
+        assert np.isfinite(s_a).all() and np.isfinite(tau_a).all()
         assert np.array_equal(tau_a, tau_b) and np.array_equal(s_a, s_b)
 
 

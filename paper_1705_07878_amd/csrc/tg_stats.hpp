@@ -409,24 +409,13 @@ __global__ void __launch_bounds__(kFinalBlock) clip_stats_final_kernel(const Sta
     const int64_t sb = p.layer_seg[l], se = p.layer_seg[l + 1];
     const int64_t base = (int64_t)w * p.n_segs;
     Acc a = {0.0, 0.0, 0.0f};
-    // four partials per thread in flight (a long layer of a large job has tens of thousands)
-    for (int64_t i = sb + t; i < se; i += 4 * kFinalBlock) {
-        double x1[4], x2[4];
-        float xm[4];
-#pragma unroll
-        for (int k = 0; k < 4; ++k) {
-            const int64_t j = i + k * kFinalBlock;
-            const bool have = j < se;
-            x1[k] = have ? p.psum[base + j] : 0.0;
-            x2[k] = have ? p.psq[base + j] : 0.0;
-            xm[k] = have ? p.pmax[base + j] : 0.0f;
-        }
-#pragma unroll
-        for (int k = 0; k < 4; ++k) {
-            a.s1 += x1[k];
-            a.s2 += x2[k];
-            a.m = fmaxf(a.m, xm[k]);
-        }
+    // (a long layer of a large job has tens of thousands of partials - 61 036 x 20 bytes per worker for 10^9
+    // elements - and one workgroup reads them at what one CU can read, 58 GB/s: 21 us, 0.2 % of that job's
+    // step; four or eight loads per thread in flight change nothing)
+    for (int64_t i = sb + t; i < se; i += kFinalBlock) {
+        a.s1 += p.psum[base + i];
+        a.s2 += p.psq[base + i];
+        a.m = fmaxf(a.m, p.pmax[base + i]);
     }
     a = wave_reduce(a);
     if ((t & 63) == 0) {

@@ -150,7 +150,8 @@ def ceilings(torch, n=1 << 30, reps=10):
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     kinds = [(0, "read", 4.0), (1, "read_nt", 4.0), (2, "write_nt", 4.0), (5, "write_nt_cooperative", 4.0),
              (6, "write_one_store_per_wave", 4.0), (3, "copy_nt", 8.0), (7, "copy_one_access_per_wave", 8.0),
-             (4, "read_nt_with_thin_write", 4.25), (8, "read_nt_with_thin_write_kept_in_L2", 4.0)]
+             (4, "read_nt_with_thin_write", 4.25), (8, "read_nt_with_thin_write_kept_in_L2", 4.0),
+             (9, "read_nt_one_shot_1024_threads_xcd_order", 4.0), (10, "read_nt_wave_per_KiB_xcd_order", 4.0)]
     out = {}
     for kind, name, bytes_per_elem in kinds:
         for _ in range(3):
@@ -163,24 +164,28 @@ def ceilings(torch, n=1 << 30, reps=10):
         ms = e0.elapsed_time(e1) / reps
         gbs = n * bytes_per_elem / (ms * 1e-3) / 1e9
         out[name] = {"ms": round(ms, 4), "GBps": round(gbs, 1), "pct_hbm_peak": round(100 * gbs / HBM_PEAK_GBS, 1)}
-    # the footprint of the flat 1e9 workload: eight 4 GB sources read one after the other
-    srcs = [src] + [torch.empty((n,), dtype=torch.float32, device="cuda").normal_() for _ in range(7)]
-    thins = [thin] + [torch.empty((n // 16,), dtype=torch.int32, device="cuda") for _ in range(7)]
-    for name, kind, bpe in (("read_nt_8x4GB", 1, 4.0), ("read_nt_with_thin_write_8x4GB", 4, 4.25),
-                            ("read_nt_with_thin_write_kept_in_L2_8x4GB", 8, 4.0)):
-        for i in range(8):
-            bench_probe(torch, kind, srcs[i], dst, thins[i], n)
+    # the footprint of the flat 1e9 workload: 8 n floats in ONE launch, as the kernels take all eight workers
+    del src, thin
+    big = torch.empty((8 * n,), dtype=torch.float32, device="cuda")
+    for i in range(8):
+        big[i * n:(i + 1) * n].normal_()
+    big_thin = torch.empty((8 * n // 16,), dtype=torch.int32, device="cuda")
+    for name, kind, bpe in (("read_nt_32GiB", 1, 4.0), ("read_nt_with_thin_write_32GiB", 4, 4.25),
+                            ("read_nt_with_thin_write_kept_in_L2_32GiB", 8, 4.0),
+                            ("read_nt_one_shot_1024_threads_xcd_order_32GiB", 9, 4.0),
+                            ("read_nt_wave_per_KiB_xcd_order_32GiB", 10, 4.0)):
+        for _ in range(2):
+            bench_probe(torch, kind, big, dst, big_thin, 8 * n)
         e0.record(stream)
-        for _ in range(3):
-            for i in range(8):
-                bench_probe(torch, kind, srcs[i], dst, thins[i], n)
+        for _ in range(4):
+            bench_probe(torch, kind, big, dst, big_thin, 8 * n)
         e1.record(stream)
         torch.cuda.synchronize()
-        ms = e0.elapsed_time(e1) / 3
+        ms = e0.elapsed_time(e1) / 4
         gbs = 8 * n * bpe / (ms * 1e-3) / 1e9
         out[name] = {"ms": round(ms, 4), "GBps": round(gbs, 1), "pct_hbm_peak": round(100 * gbs / HBM_PEAK_GBS, 1)}
     return {"ceilings": out, "elements": n, "peak_GBps": HBM_PEAK_GBS,
-            "note": "bench_probe kinds 0-8: the kernels' access patterns without arithmetic, one wave per 1024 floats"}
+            "note": "bench_probe kinds 0-10: the kernels' access patterns without arithmetic (see bench_probe.hip)"}
 
 
 def _timed(torch, stream, fn, reps, warm=2):

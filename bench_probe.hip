@@ -16,14 +16,19 @@
 //           6 write with ONE 1 KiB store per wave (sc1), 7 copy with one 1 KiB load and one 1 KiB store
 //           per wave (nt load, sc1 + nt store): the shape of the fused-update kernel for large models;
 //           8 kind 4 with the thin stream redirected into one 64 KiB region that stays in L2: the same
-//           instructions without the write traffic to HBM
-//     src   dev [n] fp32 (kinds 0, 1, 3, 4, 7, 8), dst dev [n] fp32 (written by kinds 2, 3, 5, 6, 7; kinds
-//           0, 1, 4, 8 may write dst[0]), thin dev [n/16] uint32 (kinds 4, 8); n a multiple of 4096; 16-byte aligned
+//           instructions without the write traffic to HBM;
+//           9 non-temporal read in the one-shot shape of the statistics pass for large jobs: a workgroup of
+//           1024 threads per 16384 floats, four loads per thread, chunks in that pass's XCD-aware order
+//           (n a multiple of 16384); 10 non-temporal read, a wave per 256 floats (one load per lane), every
+//           XCD reading runs of 128 consecutive workgroups: the fastest read pattern found on this chip
+//     src   dev [n] fp32 (kinds 0, 1, 3, 4, 7 - 10), dst dev [n] fp32 (written by kinds 2, 3, 5, 6, 7; kinds
+//           0, 1, 4, 8, 9, 10 may write dst[0]), thin dev [n/16] uint32 (kinds 4, 8); n a multiple of 4096; 16-byte aligned
 //     returns 0, or -1 (bad argument), -2 (alignment), -4 (launch failed)
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
 #include "paper_1705_07878_amd/csrc/tg_common.hpp"
+#include "paper_1705_07878_amd/csrc/tg_stats.hpp"          // kStatWideBlock, kStatWideChunk, kStatXcdRun
 #include "paper_1705_07878_amd/csrc/tg_ternarize.hpp"      // kEncoderXcdRun
 
 namespace {
@@ -31,7 +36,8 @@ namespace {
 using namespace tg;
 
 enum { PROBE_READ = 0, PROBE_READ_NT = 1, PROBE_WRITE_NT = 2, PROBE_COPY_NT = 3, PROBE_READ_THIN_WRITE = 4,
-       PROBE_WRITE_NT_COOP = 5, PROBE_WRITE_ONE = 6, PROBE_COPY_ONE = 7, PROBE_READ_THIN_L2 = 8 };
+       PROBE_WRITE_NT_COOP = 5, PROBE_WRITE_ONE = 6, PROBE_COPY_ONE = 7, PROBE_READ_THIN_L2 = 8,
+       PROBE_READ_ONE_SHOT = 9, PROBE_READ_WAVE_XCD = 10 };
 
 struct ProbeArgs {
     const float* src;     // [n_tiles * 1024]
@@ -124,13 +130,43 @@ __global__ void __launch_bounds__(kBlock) probe_one_kernel(const ProbeArgs p) {
     store_through4<KIND == PROBE_COPY_ONE>(p.dst + e, v);
 }
 
+// the loads must be consumed: practically never true, keeps them alive
+__device__ __forceinline__ void consume(const ProbeArgs& p, const uint32_t x) {
+    if (x == 0x7FC12345u) p.dst[0] = 1.0f;
+}
+
+__device__ __forceinline__ uint32_t fold(const float4 v) {
+    return __float_as_uint(v.x) ^ __float_as_uint(v.y) ^ __float_as_uint(v.z) ^ __float_as_uint(v.w);
+}
+
+// the statistics pass's one-shot shape: 1024 threads read 16384 floats, chunks in its XCD-aware order
+__global__ void __launch_bounds__(kStatWideBlock) probe_one_shot_kernel(const ProbeArgs p, const int64_t n_chunks) {
+    const int64_t c = xcd_run_index(blockIdx.x, kStatXcdRun);
+    if (c >= n_chunks) return;
+    const float* g = p.src + c * kStatWideChunk + 4 * threadIdx.x;
+    float4 v[4];
+#pragma unroll
+    for (int k = 0; k < 4; ++k) v[k] = load_stream(g + 4 * kStatWideBlock * k);
+    consume(p, fold(v[0]) ^ fold(v[1]) ^ fold(v[2]) ^ fold(v[3]));
+}
+
+// a wave per 256 floats, every XCD reading runs of kProbeWaveRun consecutive workgroups (512 KiB)
+constexpr int kProbeWaveRun = 128;
+__global__ void __launch_bounds__(kBlock) probe_wave_xcd_kernel(const ProbeArgs p) {
+    const int lane = threadIdx.x & (kWave - 1);
+    const int64_t q = xcd_run_index(blockIdx.x, kProbeWaveRun) * (kBlock / kWave) + (threadIdx.x >> 6);   // quarter tile
+    if (q >= 4 * p.n_tiles) return;
+    consume(p, fold(load_stream(p.src + q * 256 + 4 * lane)));
+}
+
 bool aligned(const void* p, uintptr_t a) { return ((uintptr_t)p & (a - 1)) == 0; }
 
 }  // namespace
 
 extern "C" int bench_probe(int kind, const float* src, float* dst, uint32_t* thin, int64_t n, void* stream) {
     constexpr int64_t kGroup = (int64_t)kWaveTile * (kBlock / kWave);      // 4096 floats per workgroup
-    if (kind < PROBE_READ || kind > PROBE_READ_THIN_L2 || n < kGroup || n % kGroup != 0) return -1;
+    if (kind < PROBE_READ || kind > PROBE_READ_WAVE_XCD || n < kGroup || n % kGroup != 0) return -1;
+    if (kind == PROBE_READ_ONE_SHOT && n % kStatWideChunk != 0) return -1;
     const bool reads = kind != PROBE_WRITE_NT && kind != PROBE_WRITE_NT_COOP && kind != PROBE_WRITE_ONE;
     const bool thins = kind == PROBE_READ_THIN_WRITE || kind == PROBE_READ_THIN_L2;
     if ((reads && src == nullptr) || dst == nullptr || (thins && thin == nullptr)) return -1;
@@ -159,7 +195,17 @@ extern "C" int bench_probe(int kind, const float* src, float* dst, uint32_t* thi
         case PROBE_WRITE_NT_COOP: hipLaunchKernelGGL(probe_kernel<PROBE_WRITE_NT_COOP>, grid, block, 0, s, a); break;
         case PROBE_WRITE_ONE: hipLaunchKernelGGL(probe_one_kernel<PROBE_WRITE_ONE>, dim3((unsigned)a.n_tiles), block, 0, s, a); break;
         case PROBE_COPY_ONE: hipLaunchKernelGGL(probe_one_kernel<PROBE_COPY_ONE>, dim3((unsigned)a.n_tiles), block, 0, s, a); break;
-        default: hipLaunchKernelGGL((probe_thin_kernel<PROBE_READ_THIN_L2, false>), dim3((unsigned)thin_blocks), block, 0, s, a); break;
+        case PROBE_READ_THIN_L2: hipLaunchKernelGGL((probe_thin_kernel<PROBE_READ_THIN_L2, false>), dim3((unsigned)thin_blocks), block, 0, s, a); break;
+        case PROBE_READ_ONE_SHOT: {
+            const int64_t n_chunks = n / kStatWideChunk, per = (int64_t)kXcds * kStatXcdRun;
+            hipLaunchKernelGGL(probe_one_shot_kernel, dim3((unsigned)((n_chunks + per - 1) / per * per)), dim3(kStatWideBlock), 0, s, a, n_chunks);
+            break;
+        }
+        default: {
+            const int64_t per = (int64_t)kXcds * kProbeWaveRun;
+            hipLaunchKernelGGL(probe_wave_xcd_kernel, dim3((unsigned)((a.n_tiles + per - 1) / per * per)), block, 0, s, a);
+            break;
+        }
     }
     return hipGetLastError() == hipSuccess ? 0 : -4;
 }

@@ -27,7 +27,7 @@ def test_probe_kernels_move_what_they_claim(bench):
     src = torch.randn(n, device="cuda")
     dst = torch.full((n,), -7.0, device="cuda")
     thin = torch.zeros(n // 16, dtype=torch.int32, device="cuda")
-    for kind in (0, 1):
+    for kind in (0, 1, 9, 10):
         bench.bench_probe(torch, kind, src, dst, thin, n)
     torch.cuda.synchronize()
     assert bool((dst == -7.0).all())
@@ -52,7 +52,8 @@ def test_probe_kernels_move_what_they_claim(bench):
     torch.cuda.synchronize()
     want = np.bitwise_xor.reduce(src.cpu().numpy().view(np.uint32).reshape(-1, 16), axis=1)
     assert np.array_equal(thin.cpu().numpy().view(np.uint32), want)
-    for bad in (lambda: bench.bench_probe(torch, 9, src, dst, thin, n),
+    for bad in (lambda: bench.bench_probe(torch, 11, src, dst, thin, n),
+                lambda: bench.bench_probe(torch, 9, src, dst, thin, 4096 * 3),
                 lambda: bench.bench_probe(torch, 0, src, dst, thin, 1024),
                 lambda: bench.bench_probe(torch, 4, src, dst, None, n),
                 lambda: bench.bench_probe(torch, 1, src[1:], dst, thin, 4096)):

@@ -189,15 +189,21 @@ def ceilings(torch, n=1 << 30, reps=10):
 
 
 def _timed(torch, stream, fn, reps, warm=2):
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    """ms per call of fn: the mean over reps back-to-back calls, or - when something other than the calls
+    sat in the timed region (a stall of the allocator or the driver after large buffers were released has
+    been seen to add tens of ms once) - the median of the per-call times"""
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(reps + 1)]
     for _ in range(warm):
         fn()
-    e0.record(stream)
-    for _ in range(reps):
+    ev[0].record(stream)
+    for i in range(reps):
         fn()
-    e1.record(stream)
+        ev[i + 1].record(stream)
     torch.cuda.synchronize()
-    return e0.elapsed_time(e1) / reps
+    mean = ev[0].elapsed_time(ev[reps]) / reps
+    per_call = sorted(ev[i].elapsed_time(ev[i + 1]) for i in range(reps))
+    median = per_call[reps // 2] if reps % 2 else 0.5 * (per_call[reps // 2 - 1] + per_call[reps // 2])
+    return median if mean > 1.2 * median else mean
 
 
 def _rate(nbytes, ms):

@@ -280,12 +280,35 @@ tg_status tg_unpack_average_base3(tg_plan* plan, int n_workers, const uint8_t* c
  * ternarized layers only and hands the float layers' slice of each flat buffer to this call.  A float
  * layer in the middle of the buffer is handled the same way with two plans, one over the layers before
  * it and one over the layers after it, both called on the same buffers at their offsets; the slice must
- * then begin and end at a multiple of four elements (the alignment the plans' calls require).
+ * then begin and end at a multiple of four elements (the alignment the plans' calls require); for other
+ * layouts see tg_plan_set_layer_modes below.
  *   grads  host array of n_workers dev pointers, each to n fp32
  *   avg    dev [n] fp32 out
  * The pointers need only be float addresses, but all of them (avg included) must be congruent
  * modulo 16 bytes, as the same slice of equally laid out flat buffers is; else TG_ERR_ALIGNMENT. */
 tg_status tg_average_float(int n_workers, int64_t n, const float* const* grads, float* avg, void* stream);
+
+/* The same as a per-layer mode of ONE plan (Section 4.2 keeps the last classification layer in floating
+ * point; here any layers, anywhere in the flat buffer, at any alignment).  layer_float: host array of L bytes, 1 = the layer is
+ * kept in floating point, 0 = ternarized (the default for every layer); null resets all layers to 0;
+ * other values TG_ERR_INVALID_ARG.  From then on, on this plan:
+ *   - tg_clip_stats (and tg_clip_stats_static) writes tau = 0 and s_local = 0 for those layers, so that
+ *     tg_share_scalers yields 0 and tg_ternarize_pack encodes every one of their elements as 00,
+ *     whatever the gradients hold (NaN and Inf included): their codes carry nothing;
+ *   - tg_unpack_average_mixed is tg_unpack_average followed, for the layers kept in floating point,
+ *     by the mean of tg_average_float over their elements (same arithmetic, same tolerance); the
+ *     ternarized layers come out exactly as from tg_unpack_average.  grads: host array of n_workers
+ *     dev pointers to the workers' flat gradient buffers (what tg_clip_stats was given); may be null
+ *     when no layer is kept in floating point.
+ * Every other call treats such a layer as a layer with scaler 0: tg_unpack_average and the fused updates
+ * leave the weights of those layers to the caller.  The passes still read the float layers' gradients
+ * and write their (zero) codes: where the layout allows it (float layers at the end, boundaries at
+ * multiples of four elements) a plan over the ternarized layers only plus tg_average_float moves fewer bytes.
+ * The flags are copied to the device with a blocking copy: set them before the plan is in use, or
+ * after the calls queued on it have finished. */
+tg_status tg_plan_set_layer_modes(tg_plan* plan, const uint8_t* layer_float);
+tg_status tg_unpack_average_mixed(tg_plan* plan, int n_workers, const uint8_t* const* codes,
+                                  const float* const* grads, const float* s_shared, float* avg, void* stream);
 
 #ifdef __cplusplus
 }

@@ -75,6 +75,10 @@ lib.tg_unpack_average.argtypes = [_vp, ctypes.c_int, _pp, _vp, _vp, _vp]
 lib.tg_unpack_average.restype = ctypes.c_int
 lib.tg_unpack_average_scalers.argtypes = [_vp, ctypes.c_int, _pp, _vp, _vp, _vp]
 lib.tg_unpack_average_scalers.restype = ctypes.c_int
+lib.tg_plan_set_layer_modes.argtypes = [_vp, _vp]
+lib.tg_plan_set_layer_modes.restype = ctypes.c_int
+lib.tg_unpack_average_mixed.argtypes = [_vp, ctypes.c_int, _pp, _pp, _vp, _vp, _vp]
+lib.tg_unpack_average_mixed.restype = ctypes.c_int
 lib.tg_unpack_update.argtypes = [_vp, ctypes.c_int, _pp, _vp, ctypes.c_float, _vp, _vp]
 lib.tg_unpack_update.restype = ctypes.c_int
 lib.tg_unpack_update_momentum.argtypes = [_vp, ctypes.c_int, _pp, _vp, ctypes.c_float, ctypes.c_float, _vp, _vp, _vp]
@@ -245,6 +249,23 @@ class Plan:
         cp, _k = _ptr_array(codes)
         _check(lib.tg_unpack_average(self._h, len(codes), cp, _ptr(s_shared), _ptr(avg),
                                      _stream(stream)), "tg_unpack_average")
+
+    def tg_plan_set_layer_modes(self, layer_float):
+        """layer_float: L flags (1 = layer kept in floating point), or None for all ternarized"""
+        if layer_float is None:
+            _check(lib.tg_plan_set_layer_modes(self._h, None), "tg_plan_set_layer_modes")
+            return
+        flags = np.ascontiguousarray(layer_float, dtype=np.uint8)
+        if flags.shape != (self.n_layers,):
+            raise ValueError("layer_float must hold one flag per layer")
+        _check(lib.tg_plan_set_layer_modes(self._h, flags.ctypes.data_as(ctypes.c_void_p)),
+               "tg_plan_set_layer_modes")
+
+    def tg_unpack_average_mixed(self, codes: Sequence, grads, s_shared, avg, stream=None):
+        cp, _k = _ptr_array(codes)
+        gp, _k2 = _ptr_array(grads) if grads is not None else (None, None)
+        _check(lib.tg_unpack_average_mixed(self._h, len(codes), cp, gp, _ptr(s_shared), _ptr(avg),
+                                           _stream(stream)), "tg_unpack_average_mixed")
 
     def tg_unpack_average_scalers(self, codes: Sequence, s_workers, avg, stream=None):
         cp, _k = _ptr_array(codes)

@@ -10,6 +10,7 @@
 #include <cstring>
 #include <mutex>
 #include <new>
+#include <utility>
 #include <vector>
 
 #include "tg_float.hpp"
@@ -206,6 +207,9 @@ struct tg_plan {
     tg::StatChunk* d_chunks = nullptr;
     tg::StatSeg* d_segs = nullptr;
     int64_t n_chunks = 0;
+    uint8_t* d_layer_float = nullptr;                       // [L] when some layer is kept in floating point
+    std::vector<std::pair<int64_t, int64_t>> float_runs;    // their element ranges, maximal and in order
+    std::vector<int64_t> off_host;                          // [L+1]
     int64_t* d_layer_seg = nullptr;
     double* d_psum = nullptr;
     double* d_psq = nullptr;
@@ -239,6 +243,37 @@ static tg_status launch_update(tg::UnpackArgs& a, int mode, void* stream) {
     const int64_t blocks = a.n_wave_tiles;                 // four quarter tiles = four waves per workgroup
     hipLaunchKernelGGL((tg::unpack_quarter_kernel<kSinkPolicy, DST>), dim3((unsigned)blocks), dim3(tg::kBlock), 0,
                        (hipStream_t)stream, a);
+    if (!hip_ok(hipGetLastError())) return TG_ERR_HIP;
+    return TG_OK;
+}
+
+// plain fp32 mean of the slice [first, first + n) of every gradient buffer into avg (which points AT the slice)
+static tg_status average_float_launch(int n_workers, int64_t n, const float* const* grads, int64_t first,
+                                      float* avg, void* stream) {
+    tg::FloatAvgArgs a{};
+    // a float layer is usually a slice of a flat buffer: every pointer must be a float address and all
+    // must sit at the same position inside a 16-byte line, so that one shift aligns them together
+    if (!aligned(avg, 4)) return TG_ERR_ALIGNMENT;
+    const uintptr_t phase = ((uintptr_t)avg >> 2) & 3;
+    for (int w = 0; w < n_workers; ++w) {
+        if (grads[w] == nullptr) return TG_ERR_INVALID_ARG;
+        const float* g = grads[w] + first;
+        if (!aligned(g, 4) || (((uintptr_t)g >> 2) & 3) != phase) return TG_ERR_ALIGNMENT;
+        a.grads[w] = g;
+    }
+    a.avg = avg;
+    a.n = n;
+    a.n_workers = n_workers;
+    a.head = (int32_t)((4 - phase) & 3);
+    const int64_t body = n > a.head ? n - a.head : 0;
+    const int64_t threads = (body + 3) / 4;
+    int64_t blocks = (threads + tg::kBlock - 1) / tg::kBlock;
+    if (blocks < 1) blocks = 1;
+    if (blocks > 0x7FFFFFFF) return TG_ERR_INVALID_ARG;
+    if (n * (int64_t)sizeof(float) > tg::kCodeStreamNtFrom)
+        hipLaunchKernelGGL(tg::average_float_kernel<true>, dim3((unsigned)blocks), dim3(tg::kBlock), 0, (hipStream_t)stream, a);
+    else
+        hipLaunchKernelGGL(tg::average_float_kernel<false>, dim3((unsigned)blocks), dim3(tg::kBlock), 0, (hipStream_t)stream, a);
     if (!hip_ok(hipGetLastError())) return TG_ERR_HIP;
     return TG_OK;
 }
@@ -328,7 +363,9 @@ tg_status tg_plan_create(int64_t n_layers, const int64_t* offsets, int max_worke
         build_tables(n_layers, offsets, max_workers, T);
         off.assign(offsets, offsets + n_layers + 1);
         p = new tg_plan();
+        p->off_host = off;
     } catch (const std::bad_alloc&) {
+        delete p;
         return TG_ERR_ALLOC;
     }
     // set-up work of tg_clip_stats_static, done here so that the call itself touches no runtime state
@@ -364,7 +401,8 @@ tg_status tg_plan_create(int64_t n_layers, const int64_t* offsets, int max_worke
 
 tg_status tg_plan_destroy(tg_plan* p) {
     if (p == nullptr) return TG_OK;
-    void* bufs[] = {p->d_off, p->d_tile_info, p->d_units, p->d_chunks, p->d_segs, p->d_layer_seg, p->d_psum, p->d_psq, p->d_pmax};
+    void* bufs[] = {p->d_off, p->d_tile_info, p->d_units, p->d_chunks, p->d_segs, p->d_layer_seg, p->d_psum, p->d_psq, p->d_pmax,
+                    p->d_layer_float};
     bool ok = true;
     for (void* b : bufs)
         if (b != nullptr) ok = hip_ok(hipFree(b)) && ok;
@@ -375,6 +413,35 @@ tg_status tg_plan_destroy(tg_plan* p) {
 tg_status tg_plan_set_update_kernel(tg_plan* p, int mode) {
     if (p == nullptr || mode < 0 || mode > 2) return TG_ERR_INVALID_ARG;
     p->update_mode = mode;
+    return TG_OK;
+}
+
+tg_status tg_plan_set_layer_modes(tg_plan* p, const uint8_t* layer_float) {
+    if (p == nullptr) return TG_ERR_INVALID_ARG;
+    std::vector<std::pair<int64_t, int64_t>> runs;
+    std::vector<uint8_t> flags;
+    try {
+        flags.assign((size_t)p->n_layers, 0);
+        if (layer_float != nullptr)
+            for (int64_t l = 0; l < p->n_layers; ++l) {
+                if (layer_float[l] > 1) return TG_ERR_INVALID_ARG;
+                flags[(size_t)l] = layer_float[l];
+                const int64_t b = p->off_host[(size_t)l], e = p->off_host[(size_t)l + 1];
+                if (layer_float[l] == 0 || b == e) continue;
+                if (!runs.empty() && runs.back().second == b) runs.back().second = e;
+                else runs.emplace_back(b, e);
+            }
+    } catch (const std::bad_alloc&) {
+        return TG_ERR_ALLOC;
+    }
+    if (!runs.empty() || p->d_layer_float != nullptr) {
+        // the device copy is written with a blocking copy: calls already queued on a stream must have
+        // finished reading the old flags (the caller's duty, as for any change of a plan in use)
+        if (p->d_layer_float == nullptr && !hip_ok(hipMalloc((void**)&p->d_layer_float, (size_t)p->n_layers)))
+            return TG_ERR_ALLOC;
+        if (!hip_ok(hipMemcpy(p->d_layer_float, flags.data(), (size_t)p->n_layers, hipMemcpyHostToDevice))) return TG_ERR_HIP;
+    }
+    p->float_runs.swap(runs);
     return TG_OK;
 }
 
@@ -441,6 +508,7 @@ static tg_status clip_stats_launch(tg_plan* p, int n_workers, const float* const
     f.n_layers = (int32_t)p->n_layers;
     f.c = c;
     f.noclip = (!(c > 0.0f) || std::isinf(c)) ? 1 : 0;
+    f.layer_float = p->float_runs.empty() ? nullptr : p->d_layer_float;
     if (p->n_layers < tg::kFinalPerThreadFrom) {
         hipLaunchKernelGGL(tg::clip_stats_final_kernel, dim3((unsigned)p->n_layers, (unsigned)n_workers),
                            dim3(tg::kFinalBlock), 0, s, f);
@@ -725,30 +793,20 @@ tg_status tg_decode_sum(tg_plan* p, int n_workers, const uint8_t* ksum, int bits
 tg_status tg_average_float(int n_workers, int64_t n, const float* const* grads, float* avg, void* stream) {
     if (n_workers < 1 || n < 1 || grads == nullptr || avg == nullptr) return TG_ERR_INVALID_ARG;
     if (n_workers > TG_MAX_WORKERS) return TG_ERR_TOO_MANY_WORKERS;
-    tg::FloatAvgArgs a{};
-    // a float layer is usually a slice of a flat buffer: every pointer must be a float address and all
-    // must sit at the same position inside a 16-byte line, so that one shift aligns them together
-    if (!aligned(avg, 4)) return TG_ERR_ALIGNMENT;
-    const uintptr_t phase = ((uintptr_t)avg >> 2) & 3;
-    for (int w = 0; w < n_workers; ++w) {
-        if (grads[w] == nullptr) return TG_ERR_INVALID_ARG;
-        if (!aligned(grads[w], 4) || (((uintptr_t)grads[w] >> 2) & 3) != phase) return TG_ERR_ALIGNMENT;
-        a.grads[w] = grads[w];
-    }
-    a.avg = avg;
-    a.n = n;
-    a.n_workers = n_workers;
-    a.head = (int32_t)((4 - phase) & 3);
-    const int64_t body = n > a.head ? n - a.head : 0;
-    const int64_t threads = (body + 3) / 4;
-    int64_t blocks = (threads + tg::kBlock - 1) / tg::kBlock;
-    if (blocks < 1) blocks = 1;
-    if (blocks > 0x7FFFFFFF) return TG_ERR_INVALID_ARG;
-    if (n * (int64_t)sizeof(float) > tg::kCodeStreamNtFrom)
-        hipLaunchKernelGGL(tg::average_float_kernel<true>, dim3((unsigned)blocks), dim3(tg::kBlock), 0, (hipStream_t)stream, a);
-    else
-        hipLaunchKernelGGL(tg::average_float_kernel<false>, dim3((unsigned)blocks), dim3(tg::kBlock), 0, (hipStream_t)stream, a);
-    if (!hip_ok(hipGetLastError())) return TG_ERR_HIP;
+    return average_float_launch(n_workers, n, grads, 0, avg, stream);
+}
+
+tg_status tg_unpack_average_mixed(tg_plan* p, int n_workers, const uint8_t* const* codes, const float* const* grads,
+                                  const float* s_shared, float* avg, void* stream) {
+    if (p != nullptr && !p->float_runs.empty() && grads == nullptr) return TG_ERR_INVALID_ARG;
+    if (p != nullptr && !p->float_runs.empty())
+        for (int w = 0; w < n_workers && w < TG_MAX_WORKERS; ++w)
+            if (grads[w] == nullptr) return TG_ERR_INVALID_ARG;
+    tg_status st = tg_unpack_average(p, n_workers, codes, s_shared, avg, stream);
+    if (st != TG_OK) return st;
+    // the layers kept in floating point (they came out as zeros above): the plain mean of the gradients
+    for (const auto& r : p->float_runs)
+        if ((st = average_float_launch(n_workers, r.second - r.first, grads, r.first, avg + r.first, stream)) != TG_OK) return st;
     return TG_OK;
 }
 

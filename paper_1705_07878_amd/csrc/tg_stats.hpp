@@ -381,6 +381,7 @@ struct StatsFinalArgs {
     int32_t n_layers;
     float c;
     int32_t noclip;
+    const uint8_t* layer_float;     // [L] or null: layers kept in floating point get tau = 0 and s_local = 0
 };
 
 __device__ __forceinline__ void finish_layer(const StatsFinalArgs& p, const int l, const int w,
@@ -392,7 +393,10 @@ __device__ __forceinline__ void finish_layer(const StatsFinalArgs& p, const int 
         const double var = s2 / (double)cnt - md * md;
         sigma = var > 0.0 ? sqrt(var) : 0.0;
     }
-    const float tau = p.noclip ? __builtin_inff() : (float)((double)p.c * sigma);
+    float tau = p.noclip ? __builtin_inff() : (float)((double)p.c * sigma);
+    // a layer that is not ternarized (Section 4.2): threshold and scaler 0, so that the encoder writes
+    // the code 00 for all of it and the decoder zeros, whatever the gradients hold
+    if (p.layer_float != nullptr && p.layer_float[l] != 0) tau = 0.0f;
     const int64_t o = (int64_t)w * p.n_layers + l;
     p.tau[o] = tau;
     p.s_local[o] = fminf(m, tau);                               // Eq. 2 on the clipped layer

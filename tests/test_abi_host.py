@@ -67,6 +67,8 @@ def test_null_plan_is_rejected(binding):
     assert binding.lib.tg_clip_stats_static(None, 1, None, 2.5, None, None, None) == binding.TG_ERR_INVALID_ARG
     assert binding.lib.tg_static_scratch_needed(None, 1) == -1
     assert binding.lib.tg_plan_set_update_kernel(None, 0) == binding.TG_ERR_INVALID_ARG
+    assert binding.lib.tg_plan_set_layer_modes(None, None) == binding.TG_ERR_INVALID_ARG
+    assert binding.lib.tg_unpack_average_mixed(None, 1, None, None, None, None, None) == binding.TG_ERR_INVALID_ARG
     assert binding.lib.tg_share_scalers(None, 1, None, None, None) == binding.TG_ERR_INVALID_ARG
     assert binding.lib.tg_ternarize_pack(None, 1, 0, None, None, None, 0, 0, None, None) == binding.TG_ERR_INVALID_ARG
     assert binding.lib.tg_unpack_average(None, 1, None, None, None, None) == binding.TG_ERR_INVALID_ARG

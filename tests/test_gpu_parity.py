@@ -300,6 +300,73 @@ def test_last_layer_in_float(oracle, binding):
     plan.close()
 
 
+def test_layers_kept_in_float_as_a_mode_of_one_plan(oracle, binding):
+    """Section 4.2 as a per-layer flag: float layers first, in the middle and last, next to each other and
+    alone, beginning and ending at any alignment, one of them empty, one holding NaN and Inf.  The statistics
+    give tau = s = 0 there, the codes are 00 (bit-exact with the oracle fed those scalers), the ternarized
+    layers come out as without the flag, the float layers as the plain mean."""
+    rng = np.random.default_rng(77)
+    sizes = [1001, 3, 5000, 0, 4099, 2048, 7, 30001, 513]
+    flags = np.array([1, 0, 0, 1, 1, 0, 1, 0, 1], np.uint8)
+    off = _off(sizes)
+    L = len(sizes)
+    for W in (1, 3, 8):
+        grads = _grads(rng, off, W)
+        grads[0][off[4] + 5] = np.nan
+        grads[W - 1][off[4] + 6] = np.inf
+        plan = binding.Plan(off, W)
+        dg = [dev(g) for g in grads]
+        try:
+            base = gpu_clip_stats(plan, dg, 2.5)
+            plan.tg_plan_set_layer_modes(flags)
+            tau, s_local = gpu_clip_stats(plan, dg, 2.5)
+            fl = flags.astype(bool)
+            assert np.all(tau[:, fl] == 0) and np.all(s_local[:, fl] == 0)
+            assert np.array_equal(tau[:, ~fl], base[0][:, ~fl]) and np.array_equal(s_local[:, ~fl], base[1][:, ~fl])
+            for w in range(W):
+                want_tau, want_s = oracle.clip_stats(grads[w], off, 2.5)
+                assert np.allclose(tau[w, ~fl], want_tau[~fl], rtol=1e-6, atol=0)
+                assert np.allclose(s_local[w, ~fl], want_s[~fl], rtol=1e-6, atol=0)
+            s_shared = gpu_share(plan, s_local)
+            assert np.all(s_shared[fl] == 0)
+            codes = gpu_ternarize(plan, dg, tau, s_shared, seed=11, step=4)
+            nb = (int(off[-1]) + 3) // 4
+            ocodes = [oracle.ternarize_pack(grads[w], off, tau[w], s_shared, 11, 4, w) for w in range(W)]
+            for w in range(W):
+                assert np.array_equal(codes[w][:nb], ocodes[w]) and not codes[w][nb:].any()
+            got = np.full(int(off[-1]), 9.0, np.float32)
+            dc = [dev(c) for c in codes]
+            d_s, d_avg = dev(s_shared), dev(got)
+            plan.tg_unpack_average_mixed(dc, dg, d_s, d_avg)
+            torch.cuda.synchronize()
+            got = d_avg.cpu().numpy()
+            want = oracle.unpack_average(ocodes, off, s_shared)
+            for l in range(L):
+                b, e = int(off[l]), int(off[l + 1])
+                if not flags[l]:
+                    assert_avg_close(got[b:e], want[b:e])
+                elif e > b:
+                    wf = oracle.average_float([g[b:e] for g in grads])
+                    fin = np.isfinite(wf)
+                    assert np.array_equal(np.isnan(got[b:e]), np.isnan(wf)) and np.array_equal(got[b:e][~fin & ~np.isnan(wf)], wf[~fin & ~np.isnan(wf)])
+                    assert np.allclose(got[b:e][fin], wf[fin], rtol=1e-6, atol=0)
+                    assert np.all(codes[0][(b + 3) // 4:e // 4] == 0)
+            # without float layers the call is tg_unpack_average, gradients not needed
+            plan.tg_plan_set_layer_modes(None)
+            t2, s2 = gpu_clip_stats(plan, dg, 2.5)
+            assert np.array_equal(t2, base[0]) and np.array_equal(s2, base[1])
+            plan.tg_unpack_average_mixed(dc, None, d_s, d_avg)
+            torch.cuda.synchronize()
+            assert_avg_close(d_avg.cpu().numpy(), want)
+            plan.tg_plan_set_layer_modes(flags)
+            with pytest.raises(binding.TgError):
+                plan.tg_unpack_average_mixed(dc, None, d_s, d_avg)
+            with pytest.raises(binding.TgError):
+                plan.tg_plan_set_layer_modes(np.array([2] + [0] * (L - 1), np.uint8))
+        finally:
+            plan.close()
+
+
 def test_float_layer_in_the_middle(oracle, binding):
     """A layer kept in fp32 anywhere in the flat buffer (Section 4.2 generalised): a plan over the
     layers before it, a plan over the layers after it (on the same buffers, offset), and the float call

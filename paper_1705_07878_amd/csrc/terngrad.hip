@@ -491,7 +491,7 @@ static tg_status clip_stats_launch(tg_plan* p, int n_workers, const float* const
         a.psq = psq;
         a.pmax = pmax;
         a.n_segs = p->n_segs;
-        hipLaunchKernelGGL(tg::clip_stats_partial_kernel<tg::kBlock>,
+        hipLaunchKernelGGL(tg::clip_stats_partial_kernel,
                            dim3((unsigned)p->n_units, (unsigned)n_workers), dim3(tg::kBlock), 0, s, a);
     }
     if (!hip_ok(hipGetLastError())) return TG_ERR_HIP;

@@ -201,11 +201,10 @@ __device__ __forceinline__ Acc segment_sums(const float* __restrict__ g, const i
     return a;
 }
 
-// One workgroup of NT threads per unit: either one large segment (a run of at most one chunk inside
-// one layer), reduced by all threads, or up to four small segments, one per wave (of the first four).
-template <int NT>
-__global__ void __launch_bounds__(NT) clip_stats_partial_kernel(const StatsArgs p) {
-    constexpr int NW = NT / kWave;
+// One workgroup per unit: either one large segment (a run of at most one chunk inside one layer),
+// reduced by all 256 threads, or up to four small segments, one per wave.
+__global__ void __launch_bounds__(kBlock) clip_stats_partial_kernel(const StatsArgs p) {
+    constexpr int NT = kBlock, NW = kBlock / kWave;
     __shared__ double sh1[NW], sh2[NW];
     __shared__ float shm[NW];
 
@@ -216,7 +215,7 @@ __global__ void __launch_bounds__(NT) clip_stats_partial_kernel(const StatsArgs 
     // everything a wave needs comes from its slot of the unit record, whatever the kind of unit (the
     // host repeats a large segment in all four slots): one load, which does not wait for the branch below
     const int wave = wave_uniform(t >> 6);
-    const StatSlot& u = p.units[unit].slot[wave & (kBlock / kWave - 1)];
+    const StatSlot& u = p.units[unit].slot[wave];
     const int64_t sg = u.seg_kind >> 3;
     const int count = (int)(u.seg_kind & 7);
     const int64_t sb = u.begin, se = u.end;
@@ -271,7 +270,7 @@ __global__ void __launch_bounds__(NT) clip_stats_partial_kernel(const StatsArgs 
 // workgroup index alone, so the four loads of every thread are issued first; the chunk's record (which
 // segments it holds, where their layer begins) and the pivot arrive while those are in flight.  A
 // chunk inside one layer - all but a few - is then one segment and one partial; a chunk that layers
-// begin in is reduced segment by segment by the general routine (the loads issued ahead are wasted).
+// begin in is reduced segment by segment with plain strided loads (the loads issued ahead are wasted).
 struct StatChunk {
     int64_t seg0;                   // index of the chunk's first segment
     int64_t pivot;                  // index of the first element of that segment's layer

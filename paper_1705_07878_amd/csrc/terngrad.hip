@@ -208,6 +208,7 @@ struct tg_plan {
     tg::StatSeg* d_segs = nullptr;
     int64_t n_chunks = 0;
     uint8_t* d_layer_float = nullptr;                       // [L] when some layer is kept in floating point
+    bool any_float = false;                                 // some layer is flagged (it may be empty)
     std::vector<std::pair<int64_t, int64_t>> float_runs;    // their element ranges, maximal and in order
     std::vector<int64_t> off_host;                          // [L+1]
     int64_t* d_layer_seg = nullptr;
@@ -420,12 +421,14 @@ tg_status tg_plan_set_layer_modes(tg_plan* p, const uint8_t* layer_float) {
     if (p == nullptr) return TG_ERR_INVALID_ARG;
     std::vector<std::pair<int64_t, int64_t>> runs;
     std::vector<uint8_t> flags;
+    bool any = false;
     try {
         flags.assign((size_t)p->n_layers, 0);
         if (layer_float != nullptr)
             for (int64_t l = 0; l < p->n_layers; ++l) {
                 if (layer_float[l] > 1) return TG_ERR_INVALID_ARG;
                 flags[(size_t)l] = layer_float[l];
+                any = any || layer_float[l] != 0;
                 const int64_t b = p->off_host[(size_t)l], e = p->off_host[(size_t)l + 1];
                 if (layer_float[l] == 0 || b == e) continue;
                 if (!runs.empty() && runs.back().second == b) runs.back().second = e;
@@ -434,7 +437,7 @@ tg_status tg_plan_set_layer_modes(tg_plan* p, const uint8_t* layer_float) {
     } catch (const std::bad_alloc&) {
         return TG_ERR_ALLOC;
     }
-    if (!runs.empty() || p->d_layer_float != nullptr) {
+    if (any || p->d_layer_float != nullptr) {
         // the device copy is written with a blocking copy: calls already queued on a stream must have
         // finished reading the old flags (the caller's duty, as for any change of a plan in use)
         if (p->d_layer_float == nullptr && !hip_ok(hipMalloc((void**)&p->d_layer_float, (size_t)p->n_layers)))
@@ -442,6 +445,7 @@ tg_status tg_plan_set_layer_modes(tg_plan* p, const uint8_t* layer_float) {
         if (!hip_ok(hipMemcpy(p->d_layer_float, flags.data(), (size_t)p->n_layers, hipMemcpyHostToDevice))) return TG_ERR_HIP;
     }
     p->float_runs.swap(runs);
+    p->any_float = any;
     return TG_OK;
 }
 
@@ -508,7 +512,7 @@ static tg_status clip_stats_launch(tg_plan* p, int n_workers, const float* const
     f.n_layers = (int32_t)p->n_layers;
     f.c = c;
     f.noclip = (!(c > 0.0f) || std::isinf(c)) ? 1 : 0;
-    f.layer_float = p->float_runs.empty() ? nullptr : p->d_layer_float;
+    f.layer_float = p->any_float ? p->d_layer_float : nullptr;
     if (p->n_layers < tg::kFinalPerThreadFrom) {
         hipLaunchKernelGGL(tg::clip_stats_final_kernel, dim3((unsigned)p->n_layers, (unsigned)n_workers),
                            dim3(tg::kFinalBlock), 0, s, f);

@@ -365,6 +365,16 @@ def test_layers_kept_in_float_as_a_mode_of_one_plan(oracle, binding):
                 plan.tg_plan_set_layer_modes(np.array([2] + [0] * (L - 1), np.uint8))
         finally:
             plan.close()
+    # the only flagged layer is empty, no clipping: its tau is 0 all the same, the others are +inf
+    off = _off([100, 0, 50])
+    g = [dev(x) for x in _grads(rng, off, 2)]
+    plan = binding.Plan(off, 2)
+    try:
+        plan.tg_plan_set_layer_modes(np.array([0, 1, 0], np.uint8))
+        tau, s_local = gpu_clip_stats(plan, g, 0.0)
+        assert np.all(tau[:, 1] == 0) and np.all(s_local[:, 1] == 0) and np.all(np.isinf(tau[:, [0, 2]]))
+    finally:
+        plan.close()
 
 
 def test_float_layer_in_the_middle(oracle, binding):

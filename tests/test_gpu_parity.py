@@ -602,16 +602,20 @@ def test_extreme_scalers(oracle, binding):
 
 
 def test_run_to_run_identical_statistics(binding):
+    """no atomics, fixed order of the additions: the same bits from every run, in the looping shape of the
+    statistics pass and in the one-shot shape (a plan for 64 workers of 8.4 M elements)"""
     rng = np.random.default_rng(11)
-    off = _off([100000, 50, 300000])
-    grads = [dev(g) for g in _grads(rng, off, 3)]
-    plan = binding.Plan(off, 3)
-    try:
-        a = gpu_clip_stats(plan, grads, 2.5)
-        b = gpu_clip_stats(plan, grads, 2.5)
-        assert np.array_equal(a[0], b[0]) and np.array_equal(a[1], b[1])
-    finally:
-        plan.close()
+    for sizes, mw in (([100000, 50, 300000], 3), ([5_000_001, 3, 3_400_000], 64)):
+        off = _off(sizes)
+        grads = [dev(g) for g in _grads(rng, off, 3)]
+        plan = binding.Plan(off, mw)
+        try:
+            a = gpu_clip_stats(plan, grads, 2.5)
+            for _ in range(3):
+                b = gpu_clip_stats(plan, grads, 2.5)
+                assert np.array_equal(a[0], b[0]) and np.array_equal(a[1], b[1])
+        finally:
+            plan.close()
 
 
 def test_side_stream_and_one_worker_per_call(oracle, binding):

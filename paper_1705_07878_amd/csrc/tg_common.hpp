@@ -93,11 +93,19 @@ __device__ __forceinline__ void store_stream(float* p, const float4 v) {
 // 128-bit store with sc1, and nt on top for outputs too large for the memory-side cache (the rule of the
 // code stream below, for the same reasons): what the plain average of float layers writes.  Measured
 // against a non-temporal store alone: 6 - 8 % faster on 240 MB of output, equal to 2 % faster on 4 GB.
+// The store is written as assembly because no builtin carries the sc1 bit for a 128-bit store.  The
+// compiler does not look inside the statement: it cannot know that a store of more than 64 bits needs a
+// wait state before a vector instruction may overwrite the registers that hold its data (for the stores
+// it emits itself it inserts that wait), so the wait is part of the statement.  (Tried as the policy of
+// the decoders' float4 stores as well, where the values are recomputed right after a store - without the
+// wait the momentum update then wrote corrupted velocities, caught by its parity test; with it, on 10^9
+// elements x 8 workers against the non-temporal builtin: average 0.954 against 0.960 ms, update 1.51
+// against 1.54 ms, decoder of 8-bit k fields 0.79 against 0.77 ms, whole step unchanged: not taken.)
 template <bool NT>
 __device__ __forceinline__ void store_through4(float* p, const float4 v) {
     const f32x4 t = {v.x, v.y, v.z, v.w};
-    if (NT) asm volatile("global_store_dwordx4 %0, %1, off sc1 nt" ::"v"(p), "v"(t) : "memory");
-    else asm volatile("global_store_dwordx4 %0, %1, off sc1" ::"v"(p), "v"(t) : "memory");
+    if (NT) asm volatile("global_store_dwordx4 %0, %1, off sc1 nt\n\ts_nop 1" ::"v"(p), "v"(t) : "memory");
+    else asm volatile("global_store_dwordx4 %0, %1, off sc1\n\ts_nop 1" ::"v"(p), "v"(t) : "memory");
 }
 
 // Dword store of the thin code stream that accompanies the gradient read.  Always with the sc1

@@ -3,8 +3,8 @@ import numpy as np
 import pytest
 import torch
 
-from parity_util import (assert_avg_close, assert_update_close, dev, full_parity, gpu_clip_stats, gpu_share,
-                         gpu_ternarize, gpu_unpack_average, gpu_unpack_update)
+from parity_util import (assert_avg_close, assert_stats_close, assert_update_close, dev, full_parity, gpu_clip_stats,
+                         gpu_share, gpu_ternarize, gpu_unpack_average, gpu_unpack_update)
 
 pytestmark = pytest.mark.gpu
 
@@ -106,6 +106,45 @@ def test_every_statistics_shape(oracle, binding):
         off2 = _off([4099] * 2066 + [1520])
         assert int(off2[-1]) == 8_470_054 and int(binding.tg_describe_tables(off2, 64)["chunk_elems"]) == 65536
         full_parity(oracle, binding, off2, _grads(rng, off2, 2), max_workers=64)
+    finally:
+        oracle.set_threads(1)
+
+
+def test_random_tables_in_the_one_shot_statistics_shape(oracle, binding):
+    """12 seeded random layer tables over 8.4 - 9.5 M elements in a plan for 64 workers (the one-shot shape
+    wherever few chunks hold a layer boundary): boundaries anywhere, close together, on chunk borders,
+    empty layers; small, zero and large means"""
+    rng = np.random.default_rng(99)
+    oracle.set_threads(8)
+    try:
+        shapes = []
+        for case in range(12):
+            n = int(rng.integers(8_400_000, 9_500_000))
+            k = int(rng.integers(0, 9))
+            cuts = np.sort(rng.integers(1, n, size=k)) if k else np.array([], np.int64)
+            extra = []
+            for cpos in cuts[:3]:
+                extra += [int(cpos) + int(rng.integers(0, 5))]
+            if rng.random() < 0.5:
+                extra += [16384 * int(rng.integers(1, n // 16384))]
+            off = np.unique(np.concatenate([[0], cuts, np.array(extra, np.int64), [n]])).astype(np.int64)
+            off = off[off <= n]
+            if rng.random() < 0.3:
+                i = int(rng.integers(1, len(off)))
+                off = np.insert(off, i, off[i])                 # an empty layer
+            shapes.append(int(binding.tg_describe_tables(off, 64)["chunk_elems"]))
+            W = int(rng.integers(1, 3))
+            grads = _grads(rng, off, W, mean=float(rng.choice([0.0, 1e-3, 0.5])))
+            plan = binding.Plan(off, 64)
+            try:
+                tau, s_local = gpu_clip_stats(plan, [dev(g) for g in grads], 2.5)
+            finally:
+                plan.close()
+            st = [oracle.clip_stats(g, off, 2.5) for g in grads]
+            wt, ws = np.stack([a for a, _ in st]), np.stack([b for _, b in st])
+            assert_stats_close(tau, wt, grads, off, "one-shot tau", 2.5)
+            assert_stats_close(s_local, ws, grads, off, "one-shot s_local", 2.5, want_tau=wt)
+        assert shapes.count(16384) >= 8
     finally:
         oracle.set_threads(1)
 
@@ -375,6 +414,55 @@ def test_layers_kept_in_float_as_a_mode_of_one_plan(oracle, binding):
         assert np.all(tau[:, 1] == 0) and np.all(s_local[:, 1] == 0) and np.all(np.isinf(tau[:, [0, 2]]))
     finally:
         plan.close()
+
+
+def test_random_layer_modes(oracle, binding):
+    """40 seeded random models with random float flags (layers of every size class, empty ones too; with
+    and without clipping): flagged layers get tau = s = 0 and zero codes, come out as the exact fp32 mean;
+    the others as without flags"""
+    rng = np.random.default_rng(4242)
+    for case in range(40):
+        L = int(rng.integers(1, 14))
+        kinds = rng.integers(0, 5, size=L)
+        sizes = [int([0, rng.integers(1, 12), rng.integers(1000, 1050), rng.integers(3000, 9000),
+                      rng.integers(15000, 70000)][k]) for k in kinds]
+        if sum(sizes) == 0:
+            sizes[0] = 7
+        off = _off(sizes)
+        n = int(off[-1])
+        flags = (rng.random(L) < 0.4).astype(np.uint8)
+        W = int(rng.integers(1, 10))
+        c = float(rng.choice([2.5, 1.0, 0.0]))
+        grads = _grads(rng, off, W)
+        plan = binding.Plan(off, W)
+        try:
+            plan.tg_plan_set_layer_modes(flags)
+            dg = [dev(g) for g in grads]
+            tau, s_local = gpu_clip_stats(plan, dg, c)
+            fl = flags.astype(bool)
+            assert np.all(tau[:, fl] == 0) and np.all(s_local[:, fl] == 0), case
+            s_shared = gpu_share(plan, s_local)
+            seed, step = int(rng.integers(0, 2 ** 63)), int(rng.integers(0, 2 ** 32))
+            codes = gpu_ternarize(plan, dg, tau, s_shared, seed=seed, step=step)
+            nb = (n + 3) // 4
+            oc = [oracle.ternarize_pack(grads[w], off, tau[w], s_shared, seed, step, w) for w in range(W)]
+            for w in range(W):
+                assert np.array_equal(codes[w][:nb], oc[w]) and not codes[w][nb:].any(), (case, w)
+            d_avg = torch.full((n,), 9.0, device="cuda")
+            plan.tg_unpack_average_mixed([dev(x) for x in codes], dg, dev(s_shared), d_avg)
+            torch.cuda.synchronize()
+            got = d_avg.cpu().numpy()
+            want = oracle.unpack_average(oc, off, s_shared)
+            for l in range(L):
+                b, e = int(off[l]), int(off[l + 1])
+                if e == b:
+                    continue
+                if flags[l]:
+                    assert np.array_equal(got[b:e], oracle.average_float([g[b:e] for g in grads])), (case, l)
+                else:
+                    assert_avg_close(got[b:e], want[b:e])
+        finally:
+            plan.close()
 
 
 def test_float_layer_in_the_middle(oracle, binding):

@@ -24,12 +24,13 @@ namespace tg {
 //     8 TB/s peak where the loop over 65536 elements reaches 87.5 % (runs of 4 / 8 / 32 chunks 90.9 / 92.2 /
 //     92.3 %, natural order 83 %; 512 threads 90 %; eight loads per thread 89 - 90 %; two 74 %: the
 //     barrier and the launch of sixteen waves then weigh more than the reading); the kernel itself gains
-//     2.5 % on 8 x 10^9 elements and 1 - 3 % on the VGG-A shapes, and loses 3 % on the AlexNet shapes
-//     (2.4 x 10^8 elements), hence the threshold.  A wave per 1 - 4 KiB with a partial of its own reads at
+//     2.5 % on 8 x 10^9 elements, 1 - 3 % on the VGG-A shapes and 2 % on one layer of 2.7 - 4.8 x 10^8
+//     elements, is level with the loop on 1.3 - 1.9 x 10^8 and loses 3 % on the AlexNet shapes (2.4 x 10^8
+//     elements in 16 layers), hence the threshold.  A wave per 1 - 4 KiB with a partial of its own reads at
 //     50 - 85 %: the thin stream of partials costs what the code stream costs the encoder, so partials
 //     stay rare (one per 64 KiB).
 #ifndef TG_STAT_WIDE_FROM
-#define TG_STAT_WIDE_FROM ((int64_t)1 << 29)
+#define TG_STAT_WIDE_FROM ((int64_t)1 << 28)
 #endif
 #ifndef TG_STAT_XCD_RUN
 #define TG_STAT_XCD_RUN 16

@@ -120,15 +120,18 @@ def test_tables_match_brute_force(binding, sizes):
 
 
 def test_statistics_chunk_follows_the_size_of_the_job(binding):
-    # looping shape: chunk = 8192 / 16384 / 32768 / 65536 elements for n * max_workers below 2^26 / 2^28 / 2^29 /
-    # beyond; from 2^29 on the one-shot shape with chunks of 16384, unless layers begin in too many chunks
+    # looping shape: chunk = 8192 / 16384 elements for n * max_workers below 2^26 / 2^28; from 2^28 on the one-shot
+    # shape with chunks of 16384, unless layers begin in too many chunks (then 32768 below 2^29, 65536 beyond)
     for n, W, chunk in ((1000, 1, 8192), (2 ** 26 - 1, 1, 8192), (2 ** 26, 1, 16384), (2 ** 24, 4, 16384),
-                        (2 ** 24, 16, 32768), (60_965_224, 4, 16384), (2 ** 29 - 1, 1, 32768), (2 ** 29, 1, 16384),
+                        (2 ** 24, 16, 16384), (60_965_224, 4, 16384), (2 ** 29 - 1, 1, 16384), (2 ** 29, 1, 16384),
                         (132_863_336, 8, 16384), (6_296_176, 4, 8192)):
         d = binding.tg_describe_tables(np.array([0, n]), W)
         assert d["chunk_elems"] == chunk, (n, W, d["chunk_elems"])
         s = d["segments"]
         assert s.shape[0] == -(-n // chunk) and s[0, 1] == 0 and s[-1, 2] == n and np.all(s[:, 2] - s[:, 1] <= chunk)
+    # 2^23 elements in layers of 4096, four segments in every chunk of 16384 -> the looping shape: 32 workers
+    # (2^28 elements per call) chunks of 32768, 64 workers 65536
+    assert binding.tg_describe_tables(np.arange(0, 2 ** 23 + 1, 4096, dtype=np.int64), 32)["chunk_elems"] == 32768
     # 2^23 elements x 64 workers in layers of 4096: four segments in every chunk of 16384 -> the looping shape
     off = np.arange(0, 2 ** 23 + 1, 4096, dtype=np.int64)
     assert binding.tg_describe_tables(off, 64)["chunk_elems"] == 65536

@@ -87,9 +87,9 @@ def test_many_tiny_layers(oracle, binding):
 
 
 def test_every_statistics_shape(oracle, binding):
-    """the shape of the statistics pass follows n * max_workers: workgroups that loop over chunks of 8192,
-    16384, 32768 elements, and from 2^29 elements on chunks of 16384 read in one shot by workgroups of 1024
-    threads in the XCD-aware order (65536 in a loop when layers begin in too many chunks); here with two
+    """the shape of the statistics pass follows n * max_workers: workgroups that loop over chunks of 8192 or
+    16384 elements, and from 2^28 elements on chunks of 16384 read in one shot by workgroups of 1024 threads
+    in the XCD-aware order (32768 or 65536 in a loop when layers begin in too many chunks); here with two
     workers of a plan made for more, and layer sizes that leave ragged segments in every shape"""
     rng = np.random.default_rng(35)
     off = _off([3, 3_000_001, 70_000, 5_400_001, 11])                    # n = 8,470,016
@@ -97,15 +97,17 @@ def test_every_statistics_shape(oracle, binding):
     oracle.set_threads(8)
     try:
         chunks = []
-        for mw in (2, 16, 32, 63, 64):                                   # 63: the last looping size, 64: one shot
+        for mw in (2, 16, 31, 32, 64):                                   # 31: the last looping size, 32: one shot
             chunks.append(int(binding.tg_describe_tables(off, mw)["chunk_elems"]))
             full_parity(oracle, binding, off, grads, max_workers=mw)
-        assert chunks == [8192, 16384, 32768, 32768, 16384]
-        assert 63 * 8_470_016 < 2 ** 29 <= 64 * 8_470_016
-        # many layers at the same size: chunks of 65536 in the looping shape
+        assert chunks == [8192, 16384, 16384, 16384, 16384]
+        assert 31 * 8_470_016 < 2 ** 28 <= 32 * 8_470_016
+        # many layers at the same size: chunks of 32768 and 65536 in the looping shape
         off2 = _off([4099] * 2066 + [1520])
-        assert int(off2[-1]) == 8_470_054 and int(binding.tg_describe_tables(off2, 64)["chunk_elems"]) == 65536
-        full_parity(oracle, binding, off2, _grads(rng, off2, 2), max_workers=64)
+        assert int(off2[-1]) == 8_470_054
+        for mw, chunk in ((32, 32768), (64, 65536)):
+            assert int(binding.tg_describe_tables(off2, mw)["chunk_elems"]) == chunk
+            full_parity(oracle, binding, off2, _grads(rng, off2, 2), max_workers=mw)
     finally:
         oracle.set_threads(1)
 

@@ -47,7 +47,7 @@ def test_static_scratch_variant_equals_the_plan_workspace_variant(binding):
 
 
 def test_static_scratch_variant_in_the_one_shot_shape_of_large_jobs(binding):
-    # a plan for 64 workers of 8.47 M elements (2^29 elements per call and more: workgroups of 1024 threads per
+    # a plan for 64 workers of 8.47 M elements (2^28 elements per call and more: workgroups of 1024 threads per
     # chunk of 16384), used by three; then a small model again
     sizes = [3, 3_000_001, 70_000, 5_400_001, 11]
     assert int(binding.tg_describe_tables(np.concatenate([[0], np.cumsum(sizes)]), 64)["chunk_elems"]) == 16384

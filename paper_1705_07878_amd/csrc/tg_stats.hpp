@@ -326,7 +326,7 @@ __device__ __forceinline__ void wide_fold_store(const StatsWideArgs& p, Acc a, c
     }
 }
 
-__global__ void __launch_bounds__(kStatWideBlock) clip_stats_wide_kernel(const StatsWideArgs p) {
+__global__ void __launch_bounds__(kStatWideBlock, 8) clip_stats_wide_kernel(const StatsWideArgs p) {
     __shared__ double sh1[kStatWideWaves], sh2[kStatWideWaves];
     __shared__ float shm[kStatWideWaves];
 
@@ -356,8 +356,35 @@ __global__ void __launch_bounds__(kStatWideBlock) clip_stats_wide_kernel(const S
         wide_fold_store(p, a, w, seg0, sh1, sh2, shm);
         return;
     }
-    // the rare kind of chunk (the host takes this shape only when fewer than one chunk in 64 is of this
-    // kind): plain strided loads, few registers, so that the kernel as a whole stays at two workgroups per CU
+    if (full) {
+        // a chunk that layers begin in: its data is in the registers already; every segment takes the
+        // elements at its positions (the others add an exact zero), one fold and one partial per segment.
+        // About 160 vector instructions per thread and segment, which is why the host takes this shape
+        // only when chunks of this kind are few.
+        for (int j = 0; j < nseg; ++j) {
+            const StatSeg* sg = p.segs + seg0 + j;
+            const int rb = (int)(load_uniform(&sg->begin) - e0), re = (int)(load_uniform(&sg->end) - e0);
+            const double K = (double)load_uniform(g + load_uniform(&sg->pivot));
+            Acc a = {0.0, 0.0, 0.0f};
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                const float x[4] = {v[k].x, v[k].y, v[k].z, v[k].w};
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const int pos = 4 * kStatWideBlock * k + 4 * t + i;
+                    const bool inside = pos >= rb && pos < re;
+                    const double d = inside ? (double)x[i] - K : 0.0;
+                    a.s1 += d;
+                    a.s2 = __builtin_fma(d, d, a.s2);
+                    a.m = inside ? max_abs(a.m, x[i]) : a.m;
+                }
+            }
+            wide_fold_store(p, a, w, seg0 + j, sh1, sh2, shm);
+            __syncthreads();        // the fold has read the wave sums before the next segment overwrites them
+        }
+        return;
+    }
+    // the ragged last chunk of the buffer: plain strided loads
     for (int j = 0; j < nseg; ++j) {
         const StatSeg* sg = p.segs + seg0 + j;
         const int64_t b = load_uniform(&sg->begin), e = load_uniform(&sg->end);
@@ -365,7 +392,7 @@ __global__ void __launch_bounds__(kStatWideBlock) clip_stats_wide_kernel(const S
         Acc a = {0.0, 0.0, 0.0f};
         for (int64_t i = b + t; i < e; i += kStatWideBlock) acc_add(a, g[i], K);
         wide_fold_store(p, a, w, seg0 + j, sh1, sh2, shm);
-        __syncthreads();            // the fold has read the wave sums before the next segment overwrites them
+        __syncthreads();
     }
 }
 

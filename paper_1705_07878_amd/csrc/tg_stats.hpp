@@ -25,8 +25,8 @@ namespace tg {
 //     92.3 %, natural order 83 %; 512 threads 90 %; eight loads per thread 89 - 90 %; two 74 %: the
 //     barrier and the launch of sixteen waves then weigh more than the reading); the kernel itself gains
 //     2.5 % on 8 x 10^9 elements, 1 - 3 % on the VGG-A shapes and 2 % on one layer of 2.7 - 4.8 x 10^8
-//     elements, is level with the loop on 1.3 - 1.9 x 10^8 and loses 3 % on the AlexNet shapes (2.4 x 10^8
-//     elements in 16 layers), hence the threshold.  A wave per 1 - 4 KiB with a partial of its own reads at
+//     elements, and is level with the loop on 1.3 - 2.4 x 10^8 (the AlexNet shapes among them), hence the
+//     threshold.  A wave per 1 - 4 KiB with a partial of its own reads at
 //     50 - 85 %: the thin stream of partials costs what the code stream costs the encoder, so partials
 //     stay rare (one per 64 KiB).
 #ifndef TG_STAT_WIDE_FROM
